@@ -1,0 +1,139 @@
+/*
+ * lory.h - C ABI of the MI355X (gfx950) Lory causal-segment expert-merging
+ * MoE FFN layer.
+ *
+ * The layer (paper Section 3.1, Eq. 2 and Algorithm 1; merged FFN of
+ * Section 2.2, Eq. 1; SwiGLU experts per Section 4.1):
+ *   a sequence of L tokens is cut into N = L/T segments of T tokens; the
+ *   routing weights of segment k are softmax(R(mean hidden state of segment
+ *   k-1)), the first segment routes on its own mean; the E SwiGLU experts are
+ *   merged in parameter space with those weights; the merged FFN is applied
+ *   to every token of the segment.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers on the current HIP device,
+ *     row-major contiguous (last index fastest), 16-byte aligned.
+ *   - The caller owns every buffer, including the workspace; the library
+ *     never allocates, frees or keeps a pointer past the call.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Calls only
+ *     enqueue work on that stream and return; no implicit synchronisation.
+ *   - Return value is a lory_status; nothing throws or aborts.  All argument
+ *     checks happen before the first launch; on any error return no output
+ *     buffer has been written.
+ *   - `dtype` names the storage type of X, R, the expert stacks, Y, dY, dX
+ *     and the saved activations: LORY_F32 (fp32 arithmetic throughout) or
+ *     LORY_BF16 (bf16 operands, fp32 accumulation on the matrix cores).
+ *     Routing weights w / dw and hbar are always fp32.
+ *   - Shape rules: every dimension > 0, L % T == 0 (the paper's listing uses
+ *     N = L // T with a reshape, so a ragged tail has no defined meaning),
+ *     E <= 64.  LORY_BF16 additionally needs d % 64 == 0, d_ff % 64 == 0 and
+ *     T % 64 == 0 (MFMA tile granularity).
+ */
+#ifndef LORY_H
+#define LORY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LORY_OK = 0,
+    LORY_ERR_NULL = 1,      /* a required pointer is NULL */
+    LORY_ERR_SHAPE = 2,     /* a dimension is <= 0, L % T != 0, or a granularity rule is violated */
+    LORY_ERR_DTYPE = 3,     /* unknown dtype value */
+    LORY_ERR_ALIGN = 4,     /* a pointer is not 16-byte aligned */
+    LORY_ERR_WORKSPACE = 5, /* workspace_bytes is smaller than lory_workspace_bytes() reports */
+    LORY_ERR_DEVICE = 6     /* a HIP call or kernel launch failed */
+} lory_status;
+
+typedef enum { LORY_F32 = 0, LORY_BF16 = 1 } lory_dtype;
+
+typedef enum { LORY_PASS_FWD = 0, LORY_PASS_BWD = 1 } lory_pass;
+
+/* Problem statement of Algorithm 1: x is B x L x d, E experts, segment
+ * length T; d_ff is the FFN width (the paper's d'). */
+typedef struct {
+    int32_t B, L, T, d, d_ff, E;
+    int32_t dtype; /* lory_dtype */
+} lory_shape;
+
+/* Static string for a status code (never NULL). */
+const char *lory_status_string(int status);
+
+/* Library version, "major.minor". */
+const char *lory_version(void);
+
+/*
+ * Bytes of device workspace that lory_merged_ffn_fwd (pass = LORY_PASS_FWD)
+ * or lory_merged_ffn_bwd (pass = LORY_PASS_BWD) needs for this shape.  The
+ * workspace holds only transient data (merged-weight slabs, per-segment
+ * weight-gradient slabs, activations between the two projections, partial
+ * router-weight gradients); its contents are undefined before and after a
+ * call.  Host-only: touches no device.
+ */
+int lory_workspace_bytes(const lory_shape *shape, int pass, size_t *bytes_out);
+
+/*
+ * Causal segment routing (Section 3.1, Eq. 2; Algorithm 1).
+ *   hbar[b,k,:] = (1/T) sum of X[b, kT .. kT+T-1, :]
+ *   e[b,k,:]    = softmax(hbar[b,k,:] . R)        (no bias, temperature 1)
+ *   w[b,0,:]    = e[b,0,:]       (the first segment routes on itself)
+ *   w[b,k,:]    = e[b,k-1,:]     for 1 <= k < N   (shift by one segment)
+ * in:  X [B, L, d] (dtype), R [d, E] (dtype)
+ * out: w [B*N, E] fp32, rows sum to 1; hbar_opt [B*N, d] fp32 or NULL.
+ * The stop gradient on the first segment only matters for a router
+ * backward, which is not part of this entry point.  Mean, logits and softmax
+ * are computed in fp32 for both dtypes.  Needs no workspace.
+ */
+int lory_route(const lory_shape *shape, const void *X, const void *R,
+               float *w, float *hbar_opt, void *stream);
+
+/*
+ * Merged FFN forward (Eq. 1 / Eq. 2 with SwiGLU experts):
+ *   for every segment s (S = B*N of them, T tokens each):
+ *     Wg_bar = sum_e w[s,e] Wg[e],  Wu_bar, Wd_bar likewise
+ *     G = X_s Wg_bar, U = X_s Wu_bar, A = G*sigmoid(G) (.) U, Y_s = A Wd_bar
+ * in:  X [B, L, d]; w [S, E] fp32 (any rows: lory_route's output, one-hot,
+ *      uniform ...); Wg, Wu [E, d, d_ff]; Wd [E, d_ff, d]
+ * out: Y [B, L, d]; G_save, U_save [B*L, d_ff] (dtype) or both NULL
+ * The merged parameters are never materialised as a whole: they pass through
+ * a bounded slab inside the workspace.
+ */
+int lory_merged_ffn_fwd(const lory_shape *shape, const void *X, const float *w,
+                        const void *Wg, const void *Wu, const void *Wd,
+                        void *Y, void *G_save, void *U_save,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Merged FFN backward with w treated as an independent input (chain rule on
+ * theta_bar = sum_e w_e theta_e, Eq. 2).  Per segment s, given dY_s:
+ *   dA = dY Wd_bar^T;  dWd_bar = A^T dY
+ *   dG = dA (.) U (.) sig(G)(1 + G(1 - sig(G)));  dU = dA (.) G sig(G)
+ *   dWg_bar = X^T dG;  dWu_bar = X^T dU;  dX = dG Wg_bar^T + dU Wu_bar^T
+ *   dWx[e] = sum_s w[s,e] dWx_bar(s);   dw[s,e] = sum_x <Wx[e], dWx_bar(s)>
+ * in:  X, w, Wg, Wu, Wd as for the forward; dY [B, L, d];
+ *      G_save, U_save from the forward, or both NULL to recompute them
+ * out: dX [B, L, d] (FFN path only; the router path's contribution through
+ *      the segment mean is not included); dWg, dWu [E, d, d_ff] and
+ *      dWd [E, d_ff, d] in grad_dtype (LORY_F32, or for LORY_BF16 shapes also
+ *      LORY_BF16); dw [S, E] fp32 for all segments including the first.
+ *      accumulate = 0 overwrites dWg/dWu/dWd, 1 adds to them.  dX and dw are
+ *      always overwritten.
+ * The per-segment weight gradients dWx_bar are never materialised as a
+ * whole.  Reductions across workgroups use a fixed order: two calls on the
+ * same inputs give bit-identical results.
+ */
+int lory_merged_ffn_bwd(const lory_shape *shape, const void *X, const float *w,
+                        const void *Wg, const void *Wu, const void *Wd,
+                        const void *dY, const void *G_save, const void *U_save,
+                        void *dX, void *dWg, void *dWu, void *dWd,
+                        int grad_dtype, int accumulate, float *dw,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LORY_H */

@@ -1,0 +1,204 @@
+"""Thin ctypes binding of liblory.so (C ABI: include/lory.h).
+
+Argument marshalling only: every function takes torch tensors that already
+live on the GPU, checks dtype / shape / contiguity on the host, and passes raw
+device pointers plus the current torch stream to the entry point of the same
+name.  No step of the layer is computed in Python or torch.
+
+The library is built in-tree by `python -m paper_2405_03133_amd.build`; if it
+is missing, loading fails with an error (there is no fallback path).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblory.so")
+
+LORY_OK = 0
+LORY_ERR_NULL, LORY_ERR_SHAPE, LORY_ERR_DTYPE, LORY_ERR_ALIGN, LORY_ERR_WORKSPACE, LORY_ERR_DEVICE = range(1, 7)
+LORY_F32, LORY_BF16 = 0, 1
+LORY_PASS_FWD, LORY_PASS_BWD = 0, 1
+
+EXPORTS = ("lory_status_string", "lory_version", "lory_workspace_bytes", "lory_route",
+           "lory_merged_ffn_fwd", "lory_merged_ffn_bwd")
+
+
+class LoryShape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("L", ctypes.c_int32), ("T", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("E", ctypes.c_int32),
+                ("dtype", ctypes.c_int32)]
+
+
+class LoryError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load liblory.so once; raise if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} not found: build it with `python -m paper_2405_03133_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        sp = ctypes.POINTER(LoryShape)
+        L.lory_status_string.argtypes = [ci]
+        L.lory_status_string.restype = ctypes.c_char_p
+        L.lory_version.argtypes = []
+        L.lory_version.restype = ctypes.c_char_p
+        L.lory_workspace_bytes.argtypes = [sp, ci, ctypes.POINTER(sz)]
+        L.lory_workspace_bytes.restype = ci
+        L.lory_route.argtypes = [sp, vp, vp, vp, vp, vp]
+        L.lory_route.restype = ci
+        L.lory_merged_ffn_fwd.argtypes = [sp] + [vp] * 9 + [sz, vp]
+        L.lory_merged_ffn_fwd.restype = ci
+        L.lory_merged_ffn_bwd.argtypes = [sp] + [vp] * 12 + [ci, ci, vp, vp, sz, vp]
+        L.lory_merged_ffn_bwd.restype = ci
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().lory_status_string(int(status)).decode()
+
+
+def version() -> str:
+    return lib().lory_version().decode()
+
+
+def _dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return LORY_F32
+    if t == torch.bfloat16:
+        return LORY_BF16
+    raise TypeError(f"unsupported dtype {t}")
+
+
+def make_shape(B: int, L: int, T: int, d: int, d_ff: int, E: int, dtype) -> LoryShape:
+    code = dtype if isinstance(dtype, int) else _dtype_code(dtype)
+    return LoryShape(B, L, T, d, d_ff, E, code)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("tensor must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(status: int, where: str) -> None:
+    if status != LORY_OK:
+        raise LoryError(status, where)
+
+
+def lory_workspace_bytes(shape: LoryShape, which_pass: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().lory_workspace_bytes(ctypes.byref(shape), which_pass, ctypes.byref(out)),
+           "lory_workspace_bytes")
+    return out.value
+
+
+def alloc_workspace(shape: LoryShape, which_pass: int, device="cuda") -> torch.Tensor:
+    n = lory_workspace_bytes(shape, which_pass)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+
+
+def _shape_from(X: torch.Tensor, T: int, d_ff: int, E: int) -> LoryShape:
+    B, L, d = X.shape
+    return make_shape(B, L, T, d, d_ff, E, X.dtype)
+
+
+def lory_route(X: torch.Tensor, R: torch.Tensor, T: int, w: Optional[torch.Tensor] = None,
+               hbar: Optional[torch.Tensor] = None, d_ff: int = 64) -> torch.Tensor:
+    """X [B,L,d], R [d,E] -> w [B*(L/T), E] fp32 (shifted, first-segment rule applied)."""
+    B, L, d = X.shape
+    E = R.shape[1]
+    if R.shape[0] != d or R.dtype != X.dtype:
+        raise ValueError("R must be [d, E] with the dtype of X")
+    shape = _shape_from(X, T, d_ff, E)
+    if w is None:
+        w = torch.empty((B * (L // max(T, 1)), E), dtype=torch.float32, device=X.device)
+    if w.dtype != torch.float32 or (hbar is not None and hbar.dtype != torch.float32):
+        raise TypeError("w and hbar are fp32")
+    _check(lib().lory_route(ctypes.byref(shape), _ptr(X), _ptr(R), _ptr(w), _ptr(hbar), _stream()),
+           "lory_route")
+    return w
+
+
+def lory_merged_ffn_fwd(X: torch.Tensor, w: torch.Tensor, Wg: torch.Tensor, Wu: torch.Tensor,
+                        Wd: torch.Tensor, T: int, Y: Optional[torch.Tensor] = None,
+                        G_save: Optional[torch.Tensor] = None, U_save: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y = merged SwiGLU FFN of every segment; optionally saves G and U."""
+    E, d, d_ff = Wg.shape
+    shape = _shape_from(X, T, d_ff, E)
+    for t in (Wg, Wu, Wd):
+        if t.dtype != X.dtype:
+            raise TypeError("expert stacks must have the dtype of X")
+    if tuple(Wu.shape) != (E, d, d_ff) or tuple(Wd.shape) != (E, d_ff, d) or X.shape[2] != d:
+        raise ValueError("expert stack shapes do not match")
+    if w.dtype != torch.float32 or tuple(w.shape) != (X.shape[0] * (X.shape[1] // T), E):
+        raise ValueError("w must be fp32 [S, E]")
+    if Y is None:
+        Y = torch.empty_like(X)
+    if workspace is None:
+        workspace = alloc_workspace(shape, LORY_PASS_FWD, X.device)
+    _check(lib().lory_merged_ffn_fwd(ctypes.byref(shape), _ptr(X), _ptr(w), _ptr(Wg), _ptr(Wu), _ptr(Wd),
+                                     _ptr(Y), _ptr(G_save), _ptr(U_save), _ptr(workspace),
+                                     workspace.numel(), _stream()), "lory_merged_ffn_fwd")
+    return Y
+
+
+def lory_merged_ffn_bwd(X: torch.Tensor, w: torch.Tensor, Wg: torch.Tensor, Wu: torch.Tensor,
+                        Wd: torch.Tensor, dY: torch.Tensor, T: int,
+                        G_save: Optional[torch.Tensor] = None, U_save: Optional[torch.Tensor] = None,
+                        dX: Optional[torch.Tensor] = None, dWg: Optional[torch.Tensor] = None,
+                        dWu: Optional[torch.Tensor] = None, dWd: Optional[torch.Tensor] = None,
+                        dw: Optional[torch.Tensor] = None, grad_dtype: Optional[torch.dtype] = None,
+                        accumulate: bool = False, workspace: Optional[torch.Tensor] = None
+                        ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor]:
+    """Returns (dX, dWg, dWu, dWd, dw)."""
+    E, d, d_ff = Wg.shape
+    shape = _shape_from(X, T, d_ff, E)
+    if grad_dtype is None:
+        grad_dtype = dWg.dtype if dWg is not None else torch.float32
+    if dX is None:
+        dX = torch.empty_like(X)
+    if dWg is None:
+        dWg = torch.empty(Wg.shape, dtype=grad_dtype, device=X.device)
+    if dWu is None:
+        dWu = torch.empty(Wu.shape, dtype=grad_dtype, device=X.device)
+    if dWd is None:
+        dWd = torch.empty(Wd.shape, dtype=grad_dtype, device=X.device)
+    for t in (dWg, dWu, dWd):
+        if t.dtype != grad_dtype:
+            raise TypeError("gradient stacks must all have grad_dtype")
+    if dw is None:
+        dw = torch.empty_like(w)
+    if dY.shape != X.shape or dY.dtype != X.dtype:
+        raise ValueError("dY must match X")
+    if workspace is None:
+        workspace = alloc_workspace(shape, LORY_PASS_BWD, X.device)
+    _check(lib().lory_merged_ffn_bwd(ctypes.byref(shape), _ptr(X), _ptr(w), _ptr(Wg), _ptr(Wu), _ptr(Wd),
+                                     _ptr(dY), _ptr(G_save), _ptr(U_save), _ptr(dX), _ptr(dWg), _ptr(dWu),
+                                     _ptr(dWd), _dtype_code(grad_dtype), int(bool(accumulate)), _ptr(dw),
+                                     _ptr(workspace), workspace.numel(), _stream()),
+           "lory_merged_ffn_bwd")
+    return dX, dWg, dWu, dWd, dw

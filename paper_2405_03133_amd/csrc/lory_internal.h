@@ -1,0 +1,66 @@
+// Internal declarations shared by the translation units of liblory.so.
+// Not part of the public ABI (that is include/lory.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "lory.h"
+
+namespace lory {
+
+// Derived sizes of a validated shape.
+struct Dims {
+    int B, L, T, d, dff, E;
+    int N;         // segments per sequence
+    int S;         // segments in total
+    long tokens;   // B * L
+    long D;        // d * d_ff, elements of one expert matrix
+    int dtype;
+};
+
+inline Dims make_dims(const lory_shape &s)
+{
+    Dims m;
+    m.B = s.B; m.L = s.L; m.T = s.T; m.d = s.d; m.dff = s.d_ff; m.E = s.E;
+    m.N = s.L / s.T;
+    m.S = s.B * m.N;
+    m.tokens = (long)s.B * s.L;
+    m.D = (long)s.d * s.d_ff;
+    m.dtype = s.dtype;
+    return m;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Turns the last launch error into a status.
+inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? LORY_OK : LORY_ERR_DEVICE;
+}
+
+// ---- routing (route.hip)
+int route_launch(const Dims &m, const void *X, const void *R, float *w, float *hbar,
+                 float *hbar_scratch, hipStream_t st);
+size_t route_scratch_bytes(const Dims &m);
+
+// ---- fp32 path (ffn_f32.hip)
+size_t f32_workspace_bytes(const Dims &m, int pass);
+int f32_ffn_fwd(const Dims &m, const float *X, const float *w, const float *Wg, const float *Wu,
+                const float *Wd, float *Y, float *G_save, float *U_save, void *ws, hipStream_t st);
+int f32_ffn_bwd(const Dims &m, const float *X, const float *w, const float *Wg, const float *Wu,
+                const float *Wd, const float *dY, const float *G_save, const float *U_save,
+                float *dX, float *dWg, float *dWu, float *dWd, int accumulate, float *dw,
+                void *ws, hipStream_t st);
+
+// ---- bf16 path (ffn_bf16.hip)
+size_t bf16_workspace_bytes(const Dims &m, int pass);
+int bf16_ffn_fwd(const Dims &m, const void *X, const float *w, const void *Wg, const void *Wu,
+                 const void *Wd, void *Y, void *G_save, void *U_save, void *ws, hipStream_t st);
+int bf16_ffn_bwd(const Dims &m, const void *X, const float *w, const void *Wg, const void *Wu,
+                 const void *Wd, const void *dY, const void *G_save, const void *U_save,
+                 void *dX, void *dWg, void *dWu, void *dWd, int grad_dtype, int accumulate,
+                 float *dw, void *ws, hipStream_t st);
+
+}  // namespace lory
