@@ -67,6 +67,17 @@ const char *lory_status_string(int status);
 const char *lory_version(void);
 
 /*
+ * Tuning knob (process-global, host-only): upper bound in bytes for the
+ * transient slab through which merged parameters and per-segment weight
+ * gradients pass (Eq. 2's theta_bar is produced and consumed block by block).
+ * Default 128 MiB, chosen to sit inside the 256 MB memory-side cache; the
+ * LORY_SLAB_MB environment variable sets the initial value.  Changes what
+ * lory_workspace_bytes reports, so set it before sizing a workspace.
+ * Returns LORY_ERR_SHAPE for values below 64 KiB.
+ */
+int lory_set_slab_budget(size_t bytes);
+
+/*
  * Bytes of device workspace that lory_merged_ffn_fwd (pass = LORY_PASS_FWD)
  * or lory_merged_ffn_bwd (pass = LORY_PASS_BWD) needs for this shape.  The
  * workspace holds only transient data (merged-weight slabs, per-segment

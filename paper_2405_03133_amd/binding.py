@@ -24,7 +24,7 @@ LORY_ERR_NULL, LORY_ERR_SHAPE, LORY_ERR_DTYPE, LORY_ERR_ALIGN, LORY_ERR_WORKSPAC
 LORY_F32, LORY_BF16 = 0, 1
 LORY_PASS_FWD, LORY_PASS_BWD = 0, 1
 
-EXPORTS = ("lory_status_string", "lory_version", "lory_workspace_bytes", "lory_route",
+EXPORTS = ("lory_status_string", "lory_version", "lory_set_slab_budget", "lory_workspace_bytes", "lory_route",
            "lory_merged_ffn_fwd", "lory_merged_ffn_bwd")
 
 
@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
         L.lory_status_string.restype = ctypes.c_char_p
         L.lory_version.argtypes = []
         L.lory_version.restype = ctypes.c_char_p
+        L.lory_set_slab_budget.argtypes = [sz]
+        L.lory_set_slab_budget.restype = ci
         L.lory_workspace_bytes.argtypes = [sp, ci, ctypes.POINTER(sz)]
         L.lory_workspace_bytes.restype = ci
         L.lory_route.argtypes = [sp, vp, vp, vp, vp, vp]
@@ -106,6 +108,10 @@ def _stream() -> int:
 def _check(status: int, where: str) -> None:
     if status != LORY_OK:
         raise LoryError(status, where)
+
+
+def lory_set_slab_budget(nbytes: int) -> None:
+    _check(lib().lory_set_slab_budget(int(nbytes)), "lory_set_slab_budget")
 
 
 def lory_workspace_bytes(shape: LoryShape, which_pass: int) -> int:

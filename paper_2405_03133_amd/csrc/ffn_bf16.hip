@@ -1,7 +1,317 @@
-// placeholder, replaced below
+// bf16 merged FFN forward and backward (paper Eq. 1 / Eq. 2, SwiGLU experts):
+// host-side orchestration of the MFMA kernels.
+//
+// The merged parameters of all segments (S * 3 * d * d_ff values) are never
+// held at once.  Each pass walks the expert matrices block by block; for a
+// block it (1) merges that block for ALL segments into a bounded slab (one read
+// of the expert stack, thin MFMA GEMM over the E experts), (2) runs the
+// per-segment token GEMMs that consume the slab.  The backward additionally
+// produces per-segment weight-gradient slabs that the scatter kernel folds
+// into the E expert gradients and into the router-weight gradients at once.
+// The slab budget is sized to stay resident in the 256 MB memory-side cache.
 #include "lory_internal.h"
+
+#include <stdlib.h>
+
+#include "bf16_kernels.h"
+
 namespace lory {
-size_t bf16_workspace_bytes(const Dims &, int) { return 256; }
-int bf16_ffn_fwd(const Dims &, const void *, const float *, const void *, const void *, const void *, void *, void *, void *, void *, hipStream_t) { return LORY_ERR_DTYPE; }
-int bf16_ffn_bwd(const Dims &, const void *, const float *, const void *, const void *, const void *, const void *, const void *, const void *, void *, void *, void *, void *, int, int, float *, void *, hipStream_t) { return LORY_ERR_DTYPE; }
+
+namespace {
+
+using gemm::Params;
+using k::EpiDA;
+using k::EpiGU;
+using k::EpiStore;
+using k::EpiStore2;
+using ms::MergeParams;
+using ms::Rect;
+using ms::ScatterParams;
+
+typedef uint16_t bf;
+
+size_t g_slab_budget = 0;  // 0 = not initialised yet
+
+size_t slab_budget_bytes()
+{
+    if (g_slab_budget == 0) {
+        size_t mb = 128;
+        if (const char *env = getenv("LORY_SLAB_MB")) {
+            const long v = atol(env);
+            if (v >= 1 && v <= 16384) mb = (size_t)v;
+        }
+        g_slab_budget = mb << 20;
+    }
+    return g_slab_budget;
 }
+
+// Largest multiple of `gran` that is <= limit and <= full, at least gran.
+int block_width(size_t budget, size_t bytes_per_unit, int full, int gran)
+{
+    long wdt = (long)(budget / bytes_per_unit) / gran * gran;
+    if (wdt < gran) wdt = gran;
+    if (wdt > full) wdt = full;
+    return (int)wdt;
+}
+
+struct Plan {
+    int Sc;        // segments per chunk (limits of the merge / scatter kernels)
+    int gran_f;    // granularity of d_ff blocks
+    int gran_d;    // granularity of d blocks
+    int nf_fwd, jf_fwd, nf_bwd, kf_bwd;
+    size_t act;        // bytes of one [chunk tokens, d_ff] bf16 buffer
+    size_t slab_fwd;   // bytes of the forward slab region
+    size_t slab_bwd;   // bytes of the backward slab region
+    size_t partials;   // bytes of the router-weight partial sums
+    int prow, pcol;
+};
+
+Plan make_plan(const Dims &m)
+{
+    Plan p;
+    const int cap = (m.E <= 32) ? 256 : 128;
+    p.Sc = m.S < cap ? m.S : cap;
+    p.gran_f = (m.dff % 128 == 0) ? 128 : 64;
+    p.gran_d = (m.d % 128 == 0) ? 128 : 64;
+    const size_t budget = slab_budget_bytes();
+    const size_t S = (size_t)p.Sc;
+    p.nf_fwd = block_width(budget, S * m.d * 2 * 2, m.dff, p.gran_f);
+    p.jf_fwd = block_width(budget, S * m.dff * 2, m.d, p.gran_d);
+    p.nf_bwd = block_width(budget, S * m.d * 2 * 4, m.dff, p.gran_f);
+    p.kf_bwd = block_width(budget, S * m.dff * 2 * 2, m.d, p.gran_d);
+    p.act = align_up((size_t)p.Sc * m.T * m.dff * 2, 256);
+    const size_t gu = S * m.d * p.nf_fwd * 2 * 2, dn = S * m.dff * p.jf_fwd * 2;
+    p.slab_fwd = align_up(gu > dn ? gu : dn, 256);
+    const size_t ph = S * m.d * p.nf_bwd * 2 * 4, dx = S * m.dff * p.kf_bwd * 2 * 2;
+    const size_t re = S * m.d * p.nf_bwd * 2 * 2;  // gate/up slabs when G, U are recomputed
+    size_t b = ph > dx ? ph : dx;
+    if (re > b) b = re;
+    p.slab_bwd = align_up(b, 256);
+    k::scatter_partial_dims(p.Sc, m.E, &p.prow, &p.pcol);
+    p.partials = align_up((size_t)k::scatter_grid() * 4 * p.prow * p.pcol * sizeof(float), 256);
+    return p;
+}
+
+#define LORY_TRY(expr)                                   \
+    do {                                                 \
+        if ((expr) != hipSuccess) return LORY_ERR_DEVICE; \
+    } while (0)
+
+Rect rect(long D, int pitch, int r0, int nr, int c0, int nc)
+{
+    Rect rc;
+    rc.expert_stride = D;
+    rc.pitch = pitch;
+    rc.r0 = r0;
+    rc.nr = nr;
+    rc.c0 = c0;
+    rc.nc = nc;
+    return rc;
+}
+
+hipError_t merge(hipStream_t st, const float *w, int S, int E, const bf *stack, const Rect &rc, bf *slab)
+{
+    MergeParams p;
+    p.w = w;
+    p.S = S;
+    p.E = E;
+    p.stack = stack;
+    p.rc = rc;
+    p.slab = slab;
+    p.seg_stride = (long)rc.nr * rc.nc;
+    return k::launch_merge(st, p);
+}
+
+// Gate/up projections of one d_ff column block for a chunk of segments.
+hipError_t gate_up_block(hipStream_t st, const Dims &m, int S, const bf *X, const float *w, const bf *Wg,
+                         const bf *Wu, int n0, int nf, bf *slab, bf *G, bf *U, bf *Act)
+{
+    bf *sg = slab, *su = slab + (size_t)S * m.d * nf;
+    const Rect rc = rect(m.D, m.dff, 0, m.d, n0, nf);
+    hipError_t e;
+    if ((e = merge(st, w, S, m.E, Wg, rc, sg)) != hipSuccess) return e;
+    if ((e = merge(st, w, S, m.E, Wu, rc, su)) != hipSuccess) return e;
+    Params p = {};
+    p.A[0] = X; p.a_batch[0] = (long)m.T * m.d; p.lda[0] = m.d;
+    p.B[0] = sg; p.b_batch[0] = (long)m.d * nf; p.ldb[0] = nf;
+    p.B[1] = su; p.b_batch[1] = (long)m.d * nf; p.ldb[1] = nf;
+    p.M = m.T; p.N = nf; p.K = m.d; p.batches = S;
+    EpiGU epi = {G, U, Act, m.T, m.dff, n0};
+    return k::launch_gu(st, p, epi);
+}
+
+}  // namespace
+
+int set_slab_budget(size_t bytes)
+{
+    if (bytes < ((size_t)64 << 10)) return LORY_ERR_SHAPE;
+    g_slab_budget = bytes;
+    return LORY_OK;
+}
+
+size_t bf16_workspace_bytes(const Dims &m, int pass)
+{
+    const Plan p = make_plan(m);
+    if (pass == LORY_PASS_FWD) return p.act + p.slab_fwd;
+    // dG, dU, Act, recomputed G and U, slabs, router-weight partial sums
+    return 5 * p.act + p.slab_bwd + p.partials;
+}
+
+int bf16_ffn_fwd(const Dims &m, const void *Xv, const float *w, const void *Wgv, const void *Wuv,
+                 const void *Wdv, void *Yv, void *Gv, void *Uv, void *ws, hipStream_t st)
+{
+    const Plan pl = make_plan(m);
+    const bf *X = (const bf *)Xv, *Wg = (const bf *)Wgv, *Wu = (const bf *)Wuv, *Wd = (const bf *)Wdv;
+    bf *Y = (bf *)Yv, *G = (bf *)Gv, *U = (bf *)Uv;
+    bf *Act = (bf *)ws;
+    bf *slab = (bf *)((char *)ws + pl.act);
+    const long TD = (long)m.T * m.d, TF = (long)m.T * m.dff;
+
+    for (int s0 = 0; s0 < m.S; s0 += pl.Sc) {
+        const int S = (m.S - s0 < pl.Sc) ? (m.S - s0) : pl.Sc;
+        const float *wc = w + (size_t)s0 * m.E;
+        const bf *Xc = X + (size_t)s0 * TD;
+        bf *Gc = G ? G + (size_t)s0 * TF : nullptr;
+        bf *Uc = U ? U + (size_t)s0 * TF : nullptr;
+        // gate / up projections + SwiGLU, one d_ff column block at a time
+        for (int n0 = 0; n0 < m.dff; n0 += pl.nf_fwd) {
+            const int nf = (m.dff - n0 < pl.nf_fwd) ? (m.dff - n0) : pl.nf_fwd;
+            LORY_TRY(gate_up_block(st, m, S, Xc, wc, Wg, Wu, n0, nf, slab, Gc, Uc, Act));
+        }
+        // down projection, one block of output columns at a time
+        for (int j0 = 0; j0 < m.d; j0 += pl.jf_fwd) {
+            const int jf = (m.d - j0 < pl.jf_fwd) ? (m.d - j0) : pl.jf_fwd;
+            LORY_TRY(merge(st, wc, S, m.E, Wd, rect(m.D, m.d, 0, m.dff, j0, jf), slab));
+            Params p = {};
+            p.A[0] = Act; p.a_batch[0] = TF; p.lda[0] = m.dff;
+            p.B[0] = slab; p.b_batch[0] = (long)m.dff * jf; p.ldb[0] = jf;
+            p.M = m.T; p.N = jf; p.K = m.dff; p.batches = S;
+            EpiStore epi = {Y + (size_t)s0 * TD + j0, TD, m.d};
+            LORY_TRY(k::launch_down(st, p, epi));
+        }
+    }
+    return LORY_OK;
+}
+
+int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv, const void *Wuv,
+                 const void *Wdv, const void *dYv, const void *Gv, const void *Uv, void *dXv,
+                 void *dWg, void *dWu, void *dWd, int grad_dtype, int accumulate, float *dw, void *ws,
+                 hipStream_t st)
+{
+    const Plan pl = make_plan(m);
+    const bf *X = (const bf *)Xv, *Wg = (const bf *)Wgv, *Wu = (const bf *)Wuv, *Wd = (const bf *)Wdv;
+    const bf *dY = (const bf *)dYv, *G = (const bf *)Gv, *U = (const bf *)Uv;
+    bf *dX = (bf *)dXv;
+    char *base = (char *)ws;
+    bf *dG = (bf *)base, *dU = (bf *)(base + pl.act), *Act = (bf *)(base + 2 * pl.act);
+    bf *Gr = (bf *)(base + 3 * pl.act), *Ur = (bf *)(base + 4 * pl.act);
+    bf *slab = (bf *)(base + 5 * pl.act);
+    float *partials = (float *)(base + 5 * pl.act + pl.slab_bwd);
+    const long TD = (long)m.T * m.d, TF = (long)m.T * m.dff;
+    const int grid = k::scatter_grid();
+    const int grad_f32 = (grad_dtype == LORY_F32) ? 1 : 0;
+
+    for (int s0 = 0; s0 < m.S; s0 += pl.Sc) {
+        const int S = (m.S - s0 < pl.Sc) ? (m.S - s0) : pl.Sc;
+        const float *wc = w + (size_t)s0 * m.E;
+        const bf *Xc = X + (size_t)s0 * TD;
+        const bf *dYc = dY + (size_t)s0 * TD;
+        const int acc_dW = (accumulate || s0 > 0) ? 1 : 0;
+        int partials_add = 0;
+
+        const bf *Gc, *Uc;
+        if (G && U) {
+            Gc = G + (size_t)s0 * TF;
+            Uc = U + (size_t)s0 * TF;
+        } else {
+            // the backward slab region holds four slabs of nf_bwd columns, i.e. a gate and an
+            // up slab of 2 * nf_bwd columns each
+            const int step = 2 * pl.nf_bwd;
+            for (int n0 = 0; n0 < m.dff; n0 += step) {
+                const int nf = (m.dff - n0 < step) ? (m.dff - n0) : step;
+                LORY_TRY(gate_up_block(st, m, S, Xc, wc, Wg, Wu, n0, nf, slab, Gr, Ur, nullptr));
+            }
+            Gc = Gr;
+            Uc = Ur;
+        }
+
+        // ---- d_ff blocks: dA (+ SwiGLU backward), weight-gradient slabs, scatter
+        for (int n0 = 0; n0 < m.dff; n0 += pl.nf_bwd) {
+            const int nf = (m.dff - n0 < pl.nf_bwd) ? (m.dff - n0) : pl.nf_bwd;
+            const size_t blk = (size_t)S * m.d * nf;  // elements of one slab of this block
+            bf *s_md = slab, *s_gd = slab + blk, *s_gg = slab + 2 * blk, *s_gu = slab + 3 * blk;
+            const Rect rows_d = rect(m.D, m.d, n0, nf, 0, m.d);      // rows n0.. of Wd [d_ff, d]
+            const Rect cols_f = rect(m.D, m.dff, 0, m.d, n0, nf);    // columns n0.. of Wg/Wu [d, d_ff]
+
+            // dA = dY Wd_bar^T for these d_ff columns, then dG, dU, A
+            LORY_TRY(merge(st, wc, S, m.E, Wd, rows_d, s_md));
+            {
+                Params p = {};
+                p.A[0] = dYc; p.a_batch[0] = TD; p.lda[0] = m.d;
+                p.B[0] = s_md; p.b_batch[0] = (long)nf * m.d; p.ldb[0] = m.d;
+                p.M = m.T; p.N = nf; p.K = m.d; p.batches = S;
+                EpiDA epi = {Gc, Uc, dG, dU, Act, m.T, m.dff, n0};
+                LORY_TRY(k::launch_da(st, p, epi));
+            }
+            // dWd_bar rows = A^T dY
+            {
+                Params p = {};
+                p.A[0] = Act + n0; p.a_batch[0] = TF; p.lda[0] = m.dff;
+                p.B[0] = dYc; p.b_batch[0] = TD; p.ldb[0] = m.d;
+                p.M = nf; p.N = m.d; p.K = m.T; p.batches = S;
+                EpiStore epi = {s_gd, (long)nf * m.d, m.d};
+                LORY_TRY(k::launch_dwd(st, p, epi));
+            }
+            // dWg_bar, dWu_bar columns = X^T dG, X^T dU
+            {
+                Params p = {};
+                p.A[0] = Xc; p.a_batch[0] = TD; p.lda[0] = m.d;
+                p.B[0] = dG + n0; p.b_batch[0] = TF; p.ldb[0] = m.dff;
+                p.B[1] = dU + n0; p.b_batch[1] = TF; p.ldb[1] = m.dff;
+                p.M = m.d; p.N = nf; p.K = m.T; p.batches = S;
+                EpiStore2 epi = {s_gg, s_gu, (long)m.d * nf, nf};
+                LORY_TRY(k::launch_dwgu(st, p, epi));
+            }
+            // E-way scatter and router-weight inner products
+            const bf *stacks[3] = {Wd, Wg, Wu};
+            void *grads[3] = {dWd, dWg, dWu};
+            const bf *gsl[3] = {s_gd, s_gg, s_gu};
+            const Rect rcs[3] = {rows_d, cols_f, cols_f};
+            for (int i = 0; i < 3; ++i) {
+                ScatterParams sp;
+                sp.w = wc; sp.S = S; sp.E = m.E;
+                sp.gslab = gsl[i]; sp.seg_stride = (long)rcs[i].nr * rcs[i].nc;
+                sp.stack = stacks[i]; sp.dW = grads[i]; sp.rc = rcs[i];
+                sp.grad_f32 = grad_f32; sp.accumulate = acc_dW;
+                sp.partials = partials; sp.partials_add = partials_add;
+                LORY_TRY(k::launch_scatter(st, sp, grid));
+                partials_add = 1;
+            }
+        }
+
+        // ---- dX = dG Wg_bar^T + dU Wu_bar^T, one block of d columns at a time
+        for (int k0 = 0; k0 < m.d; k0 += pl.kf_bwd) {
+            const int kf = (m.d - k0 < pl.kf_bwd) ? (m.d - k0) : pl.kf_bwd;
+            const size_t blk = (size_t)S * kf * m.dff;
+            bf *s_g = slab, *s_u = slab + blk;
+            const Rect rows = rect(m.D, m.dff, k0, kf, 0, m.dff);
+            LORY_TRY(merge(st, wc, S, m.E, Wg, rows, s_g));
+            LORY_TRY(merge(st, wc, S, m.E, Wu, rows, s_u));
+            Params p = {};
+            p.A[0] = dG; p.a_batch[0] = TF; p.lda[0] = m.dff;
+            p.A[1] = dU; p.a_batch[1] = TF; p.lda[1] = m.dff;
+            p.B[0] = s_g; p.b_batch[0] = (long)kf * m.dff; p.ldb[0] = m.dff;
+            p.B[1] = s_u; p.b_batch[1] = (long)kf * m.dff; p.ldb[1] = m.dff;
+            p.M = m.T; p.N = kf; p.K = m.dff; p.batches = S;
+            EpiStore epi = {dX + (size_t)s0 * TD + k0, TD, m.d};
+            LORY_TRY(k::launch_dx(st, p, epi));
+        }
+
+        int prow, pcol;
+        k::scatter_partial_dims(S, m.E, &prow, &pcol);
+        LORY_TRY(k::launch_dw_reduce(st, partials, grid * 4, prow, pcol, dw + (size_t)s0 * m.E, S, m.E));
+    }
+    return LORY_OK;
+}
+
+}  // namespace lory

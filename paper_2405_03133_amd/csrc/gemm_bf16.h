@@ -1,0 +1,305 @@
+// Batched bf16 MFMA GEMM core for gfx950 (one batch item = one segment of the
+// Lory layer).  Every dense contraction of the merged FFN and of its backward
+// (paper Section 3.1: o_x = FFN(h_x; theta_bar) for all tokens of a segment;
+// Appendix B counts them as 6*L*d*d' FLOPs) is an instance of
+//
+//     C_b[M,N] = sum over sources q of  A_{q,b}[M,K] * B_{q,b}[K,N]
+//
+// with fp32 accumulation on v_mfma_f32_32x32x16_bf16.
+//
+// Operand layouts, chosen per instance by template flags:
+//   A: "KC" = stored [M][K] (K contiguous)   or "MC" = stored [K][M]
+//   B: "KC" = stored [N][K] (K contiguous)   or "NC" = stored [K][N]
+// KC tiles sit in LDS as rows of 64 bf16 with an XOR swizzle of their 16-byte
+// chunks and are read with ds_read_b128.  MC/NC tiles sit in LDS as they are
+// in memory (rows of the non-contracted index, padded pitch) and are read with
+// ds_read_b64_tr_b16, which hands each lane four consecutive K values of its
+// own column, i.e. the transposition happens inside the LDS read.
+//
+// A workgroup is 256 threads = 4 wavefronts computing a BM x BN tile (times
+// NSET operand sets that share A, e.g. the gate and up projections).  K is
+// walked in steps of 64 with two LDS stages: global loads of step i+1 are
+// issued into registers before the MFMAs of step i and stored to the other
+// stage afterwards, one barrier per step.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <type_traits>
+
+namespace lory {
+namespace gemm {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;
+constexpr int BK = 64;
+
+struct Params {
+    const uint16_t *A[2];  // per source
+    long a_batch[2];       // elements between consecutive batch items
+    int lda[2];            // elements between consecutive rows of the stored matrix
+    const uint16_t *B[2];  // per operand set (NSET == 2) or per source (NSRC == 2)
+    long b_batch[2];
+    int ldb[2];
+    int M, N, K;           // per batch item; K per source
+    int batches;
+};
+
+__host__ __device__ constexpr int tr_pitch(int width) { return width * 2 + 64; }
+
+template <int BM, int BN, int NSET, bool A_MC, bool B_NC>
+struct Smem {
+    static constexpr int a_bytes = A_MC ? BK * tr_pitch(BM) : BM * 128;
+    static constexpr int b_bytes = B_NC ? BK * tr_pitch(BN) : BN * 128;
+    static constexpr int stage = a_bytes + NSET * b_bytes;
+    static constexpr int total = 2 * stage;
+};
+
+// Swizzle of the 16-byte chunk index inside a 128-byte KC row.
+__device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b)
+{
+    return __uint_as_float(((uint32_t)b) << 16);
+}
+
+// Round to nearest even; inputs here are finite.
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// ---- global -> register staging of one K step -------------------------------
+
+template <int ROWS>  // KC tile: ROWS rows of 64 bf16
+struct StageKC {
+    static constexpr int n = ROWS / 32;
+    uint4 v[n];
+    __device__ __forceinline__ void load(const uint16_t *base, int ld, int row0, int k0, int tid)
+    {
+        const int c = tid & 7;
+#pragma unroll
+        for (int i = 0; i < n; ++i) {
+            const int row = (tid >> 3) + 32 * i;
+            v[i] = *reinterpret_cast<const uint4 *>(base + (size_t)(row0 + row) * ld + k0 + c * 8);
+        }
+    }
+    __device__ __forceinline__ void store(char *lds, int tid) const
+    {
+        const int c = tid & 7;
+#pragma unroll
+        for (int i = 0; i < n; ++i) {
+            const int row = (tid >> 3) + 32 * i;
+            *reinterpret_cast<uint4 *>(lds + row * 128 + ((c ^ swz(row)) << 4)) = v[i];
+        }
+    }
+};
+
+template <int WIDTH>  // MC / NC tile: 64 rows (K) of WIDTH bf16
+struct StageTR {
+    static constexpr int n = WIDTH / 32;
+    static constexpr int cpr = WIDTH / 8;  // 16-byte chunks per row
+    uint4 v[n];
+    __device__ __forceinline__ void load(const uint16_t *base, int ld, int col0, int k0, int tid)
+    {
+#pragma unroll
+        for (int i = 0; i < n; ++i) {
+            const int idx = tid + kThreads * i;
+            const int row = idx / cpr, c = idx % cpr;
+            v[i] = *reinterpret_cast<const uint4 *>(base + (size_t)(k0 + row) * ld + col0 + c * 8);
+        }
+    }
+    __device__ __forceinline__ void store(char *lds, int tid) const
+    {
+#pragma unroll
+        for (int i = 0; i < n; ++i) {
+            const int idx = tid + kThreads * i;
+            const int row = idx / cpr, c = idx % cpr;
+            *reinterpret_cast<uint4 *>(lds + row * tr_pitch(WIDTH) + (c << 4)) = v[i];
+        }
+    }
+};
+
+// ---- LDS -> MFMA operand fragments ------------------------------------------
+
+// 32 rows x 16 K of a KC tile: lane holds row (lane & 31), K = kk*16 + (lane>>5)*8 .. +7.
+__device__ __forceinline__ bf16x8 frag_kc(const char *lds, int row0, int kk, int lane)
+{
+    const int row = row0 + (lane & 31);
+    const int c = kk * 2 + (lane >> 5);
+    return *reinterpret_cast<const bf16x8 *>(lds + row * 128 + ((c ^ swz(row)) << 4));
+}
+
+// 32 columns x 16 K of an MC/NC tile through the transposing LDS read.  Within
+// a group of 16 lanes, lane r supplies the address of row (r>>2), columns
+// 4*(r&3)..+3 of a 4x16 block and receives the 4 rows of column r.  Two reads
+// (rows +0..3 and +4..7) give the same K set per lane as frag_kc.
+template <int PITCH>
+__device__ __forceinline__ bf16x8 frag_tr(const char *lds, int col0, int kk, int lane)
+{
+    typedef __attribute__((address_space(3))) s16x4 *lds_ptr;
+    const int g = lane >> 4, r = lane & 15;
+    const int col = col0 + 16 * (g & 1) + 4 * (r & 3);
+    const int krow = kk * 16 + 8 * (g >> 1) + (r >> 2);
+    const char *p = lds + krow * PITCH + col * 2;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * PITCH));
+    union {
+        s16x4 h[2];
+        bf16x8 v;
+    } u;
+    u.h[0] = lo;
+    u.h[1] = hi;
+    return u.v;
+}
+
+// ---- the kernel ---------------------------------------------------------------
+//
+// Epi is a functor:  epi(batch, m, n, const float (&v)[NSET])  called once per
+// output element; consecutive lanes get consecutive n.
+template <int BM, int BN, int WAVES_M, int NSET, int NSRC, bool A_MC, bool B_NC, class Epi>
+__global__ __launch_bounds__(kThreads) void gemm_kernel(const Params p, const Epi epi)
+{
+    static_assert(NSET == 1 || NSRC == 1, "either two operand sets or two sources");
+    constexpr int WAVES_N = 4 / WAVES_M;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int MI = WM / 32, NI = WN / 32;
+    static_assert(MI >= 1 && NI >= 1, "wave tile must hold at least one 32x32 block");
+    using SM = Smem<BM, BN, NSET, A_MC, B_NC>;
+    constexpr int A_PITCH = tr_pitch(BM), B_PITCH = tr_pitch(BN);
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm0 = (wave / WAVES_N) * WM;
+    const int wn0 = (wave % WAVES_N) * WN;
+
+    const int tiles_n = p.N / BN;
+    const int tiles_m = p.M / BM;
+    int bid = blockIdx.x;
+    const int nt = bid % tiles_n;
+    bid /= tiles_n;
+    const int mt = bid % tiles_m;
+    const int batch = bid / tiles_m;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int ktiles = p.K / BK;
+    const int total_tiles = ktiles * NSRC;
+
+    f32x16 acc[NSET][MI][NI];
+#pragma unroll
+    for (int s = 0; s < NSET; ++s)
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[s][i][j][r] = 0.f;
+
+    typename std::conditional<A_MC, StageTR<BM>, StageKC<BM>>::type sa;
+    typename std::conditional<B_NC, StageTR<BN>, StageKC<BN>>::type sb[NSET];
+
+    auto load_tile = [&](int t) {
+        const int src = (NSRC == 2) ? (t / ktiles) : 0;
+        const int k0 = (t % ktiles) * BK;
+        const uint16_t *a = p.A[src] + (size_t)batch * p.a_batch[src];
+        sa.load(a, p.lda[src], m0, k0, tid);
+#pragma unroll
+        for (int s = 0; s < NSET; ++s) {
+            const int bi = (NSRC == 2) ? src : s;
+            const uint16_t *b = p.B[bi] + (size_t)batch * p.b_batch[bi];
+            sb[s].load(b, p.ldb[bi], n0, k0, tid);
+        }
+    };
+    auto store_tile = [&](int stage) {
+        char *base = smem + stage * SM::stage;
+        sa.store(base, tid);
+#pragma unroll
+        for (int s = 0; s < NSET; ++s) sb[s].store(base + SM::a_bytes + s * SM::b_bytes, tid);
+    };
+
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (int t = 0; t < total_tiles; ++t) {
+        const bool more = (t + 1 < total_tiles);
+        if (more) load_tile(t + 1);
+        const char *base = smem + (t & 1) * SM::stage;
+        const char *la = base;
+        const char *lb = base + SM::a_bytes;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 af[MI];
+            bf16x8 bf[NSET][NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+                if constexpr (A_MC)
+                    af[i] = frag_tr<A_PITCH>(la, wm0 + i * 32, kk, lane);
+                else
+                    af[i] = frag_kc(la, wm0 + i * 32, kk, lane);
+            }
+#pragma unroll
+            for (int s = 0; s < NSET; ++s)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    if constexpr (B_NC)
+                        bf[s][j] = frag_tr<B_PITCH>(lb + s * SM::b_bytes, wn0 + j * 32, kk, lane);
+                    else
+                        bf[s][j] = frag_kc(lb + s * SM::b_bytes, wn0 + j * 32, kk, lane);
+                }
+#pragma unroll
+            for (int s = 0; s < NSET; ++s)
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        acc[s][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[s][j],
+                                                                               acc[s][i][j], 0, 0, 0);
+        }
+        if (more) store_tile((t + 1) & 1);
+        __syncthreads();
+    }
+
+    // accumulator element r of a 32x32 block: row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int n = n0 + wn0 + j * 32 + (lane & 31);
+                float v[NSET];
+#pragma unroll
+                for (int s = 0; s < NSET; ++s) v[s] = acc[s][i][j][r];
+                epi(batch, m, n, v);
+            }
+}
+
+template <int BM, int BN, int WAVES_M, int NSET, int NSRC, bool A_MC, bool B_NC, class Epi>
+inline hipError_t launch(const Params &p, const Epi &epi, hipStream_t st)
+{
+    using SM = Smem<BM, BN, NSET, A_MC, B_NC>;
+    auto kern = gemm_kernel<BM, BN, WAVES_M, NSET, NSRC, A_MC, B_NC, Epi>;
+    static bool configured = false;  // per instantiation
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, SM::total);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const long blocks = (long)p.batches * (p.M / BM) * (p.N / BN);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kThreads), SM::total, st, p, epi);
+    return hipGetLastError();
+}
+
+}  // namespace gemm
+}  // namespace lory

@@ -45,6 +45,8 @@ const char *lory_status_string(int status)
 
 const char *lory_version(void) { return "0.1"; }
 
+int lory_set_slab_budget(size_t bytes) { return lory::set_slab_budget(bytes); }
+
 int lory_workspace_bytes(const lory_shape *shape, int pass, size_t *bytes_out)
 {
     if (!bytes_out) return LORY_ERR_NULL;

@@ -55,6 +55,7 @@ int f32_ffn_bwd(const Dims &m, const float *X, const float *w, const float *Wg, 
                 void *ws, hipStream_t st);
 
 // ---- bf16 path (ffn_bf16.hip)
+int set_slab_budget(size_t bytes);
 size_t bf16_workspace_bytes(const Dims &m, int pass);
 int bf16_ffn_fwd(const Dims &m, const void *X, const float *w, const void *Wg, const void *Wu,
                  const void *Wd, void *Y, void *G_save, void *U_save, void *ws, hipStream_t st);

@@ -148,3 +148,69 @@ def test_errors_leave_outputs_untouched():
     lb.lory_merged_ffn_fwd(X, w, Wg, Wu, Wd, cfg.T, Y=Y)
     torch.cuda.synchronize()
     assert bool(torch.isfinite(Y).all()) and not bool((Y == 7.0).all())
+
+
+# ------------------------------------------------------------------ bf16
+
+BF16_CASES = [
+    # (config, slab budget in bytes) - small budgets force several blocks and a ragged last block
+    (LoryConfig("bf16_multi_block", B=2, L=512, T=128, d=256, d_ff=576, E=8, dtype="bf16", seed=31), 1 << 20),
+    (LoryConfig("bf16_T64", B=2, L=256, T=64, d=128, d_ff=192, E=4, dtype="bf16", seed=32), 256 << 10),
+    (LoryConfig("bf16_T256_E32", B=1, L=512, T=256, d=192, d_ff=256, E=32, dtype="bf16", seed=33), 512 << 10),
+    (LoryConfig("bf16_E33", B=1, L=256, T=64, d=64, d_ff=128, E=33, dtype="bf16", seed=34), 128 << 20),
+    (LoryConfig("bf16_S40", B=5, L=512, T=64, d=64, d_ff=64, E=3, dtype="bf16", seed=35), 128 << 20),
+    (LoryConfig("bf16_one_expert", B=1, L=128, T=64, d=64, d_ff=128, E=1, dtype="bf16", seed=36), 128 << 20),
+]
+
+
+@pytest.fixture
+def default_budget():
+    yield
+    lb.lory_set_slab_budget(128 << 20)
+
+
+@pytest.mark.parametrize("cfg,budget", BF16_CASES, ids=lambda v: v.name if isinstance(v, LoryConfig) else str(v))
+def test_bf16_small_shapes(cfg, budget, default_budget):
+    lb.lory_set_slab_budget(budget)
+    t = make_inputs(cfg, structured=True)
+    got = run_layer(cfg, t)
+    ref = oracle_layer(cfg, t, got["w_used"])
+    compare(cfg, got, ref, ("w", "hbar"), 1e-5)
+    compare(cfg, got, ref, ALL, TOL["bf16"])
+
+
+def test_bf16_recompute_bf16_grads_and_accumulate(default_budget):
+    cfg = BF16_CASES[0][0]
+    lb.lory_set_slab_budget(1 << 20)
+    t = make_inputs(cfg, structured=True)
+    w1 = make_routing_weights(cfg, "peaked")
+    # no saved activations: the backward recomputes G and U; gradients stored as bf16
+    got = run_layer(cfg, t, w_override=w1, save=False, grad_dtype=torch.bfloat16)
+    ref = oracle_layer(cfg, t, w1)
+    compare(cfg, got, ref, ("Y", "dX", "dWg", "dWu", "dWd", "dw"), TOL["bf16"])
+    X, Wg, Wu, Wd, dY = (to_dev(t[k], cfg) for k in ("X", "Wg", "Wu", "Wd", "dY"))
+    w = torch.from_numpy(w1).cuda()
+    for gd in (torch.float32, torch.bfloat16):
+        base = [torch.full(Wg.shape, 0.5, dtype=gd, device="cuda"),
+                torch.full(Wu.shape, -0.25, dtype=gd, device="cuda"),
+                torch.full(Wd.shape, 2.0, dtype=gd, device="cuda")]
+        lb.lory_merged_ffn_bwd(X, w, Wg, Wu, Wd, dY, cfg.T, dWg=base[0], dWu=base[1], dWd=base[2],
+                               accumulate=True, grad_dtype=gd)
+        torch.cuda.synchronize()
+        tol = 2e-2 if gd == torch.bfloat16 else TOL["bf16"]
+        assert rel_l2(host(base[0]), ref["dWg"] + 0.5) <= tol
+        assert rel_l2(host(base[1]), ref["dWu"] - 0.25) <= tol
+        assert rel_l2(host(base[2]), ref["dWd"] + 2.0) <= tol
+
+
+def test_bf16_onehot_and_determinism(default_budget):
+    cfg = BF16_CASES[0][0]
+    lb.lory_set_slab_budget(1 << 20)
+    t = make_inputs(cfg)
+    w1 = make_routing_weights(cfg, "onehot")
+    a = run_layer(cfg, t, w_override=w1)
+    b = run_layer(cfg, t, w_override=w1)
+    ref = oracle_layer(cfg, t, w1)
+    compare(cfg, a, ref, ALL, TOL["bf16"])
+    for key in ALL:
+        assert np.array_equal(a[key], b[key]), key
