@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the Lory merged-MoE-FFN hot path on one MI355X.
+
+One step = lory_route -> lory_merged_ffn_fwd -> lory_merged_ffn_bwd over one
+batch of synthetic hidden states (inputs already resident in HBM).  Prints ONE
+JSON line: whole-job tokens/s, the roofline figures of the dominant kernel
+class (timed with HIP events inside the library on the stream it launches on),
+and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE);
+# filled in from profiles/ once measured, else None.
+TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="C4", help="workload name from paper_2405_03133_amd.inputs.CONFIGS")
+    ap.add_argument("--grad-dtype", default="bf16", choices=["bf16", "f32"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-save", action="store_true", help="do not save G/U in the forward (backward recomputes)")
+    ap.add_argument("--slab-mb", type=int, default=0)
+    ap.add_argument("--verbose", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, verbose=False):
+    """Time the fp64 oracle (route + fwd + bwd) on two segments of the same shape."""
+    import numpy as np
+    from oracle import lory_oracle as orc
+    from paper_2405_03133_amd.inputs import make_inputs
+
+    n_seg = 2
+    sample = cfg.with_(B=1, L=n_seg * cfg.T)
+    t = make_inputs(sample)
+    t64 = {k: v.astype(np.float64) for k, v in t.items()}
+    del t
+    t0 = time.perf_counter()
+    r = orc.route(t64["X"], t64["R"], sample.T)
+    f = orc.ffn_fwd(t64["X"], r["w"], t64["Wg"], t64["Wu"], t64["Wd"], sample.T)
+    g = orc.ffn_bwd(t64["X"], r["w"], t64["Wg"], t64["Wu"], t64["Wd"], t64["dY"], sample.T)
+    dt = time.perf_counter() - t0
+    del f, g
+    if verbose:
+        print(f"[cpu] oracle {sample.tokens} tokens in {dt:.2f} s", file=sys.stderr)
+    return {"value": sample.tokens / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{n_seg} segments of T={cfg.T} tokens at the full d={cfg.d}, d_ff={cfg.d_ff}, E={cfg.E} "
+                      f"(route+fwd+bwd, fp64, {dt:.1f} s)"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives are part of it)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2405_03133_amd import binding as lb
+    from paper_2405_03133_amd.inputs import CONFIGS
+
+    cfg = CONFIGS[args.config]
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    if args.slab_mb:
+        lb.lory_set_slab_budget(args.slab_mb << 20)
+    dt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    gdt = torch.float32 if (args.grad_dtype == "f32" or cfg.dtype == "f32") else torch.bfloat16
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed)
+
+    def normal(shape, sigma):
+        return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * sigma).to(dt)
+
+    X = normal((cfg.B, cfg.L, cfg.d), 1.0)
+    R = normal((cfg.d, cfg.E), 0.02)
+    Wg = normal((cfg.E, cfg.d, cfg.d_ff), 0.02)
+    Wu = normal((cfg.E, cfg.d, cfg.d_ff), 0.02)
+    Wd = normal((cfg.E, cfg.d_ff, cfg.d), 0.02)
+    dY = normal((cfg.B, cfg.L, cfg.d), 1.0)
+
+    shape = lb.make_shape(cfg.B, cfg.L, cfg.T, cfg.d, cfg.d_ff, cfg.E, dt)
+    ws_f = lb.alloc_workspace(shape, lb.LORY_PASS_FWD)
+    ws_b = lb.alloc_workspace(shape, lb.LORY_PASS_BWD)
+    w = torch.empty((cfg.S, cfg.E), dtype=torch.float32, device=dev)
+    Y = torch.empty_like(X)
+    G = U = None
+    if not args.no_save:
+        G = torch.empty((cfg.tokens, cfg.d_ff), dtype=dt, device=dev)
+        U = torch.empty_like(G)
+    dX = torch.empty_like(X)
+    dWg = torch.empty(Wg.shape, dtype=gdt, device=dev)
+    dWu = torch.empty(Wu.shape, dtype=gdt, device=dev)
+    dWd = torch.empty(Wd.shape, dtype=gdt, device=dev)
+    dw = torch.empty_like(w)
+
+    def step():
+        lb.lory_route(X, R, cfg.T, w=w, d_ff=cfg.d_ff)
+        lb.lory_merged_ffn_fwd(X, w, Wg, Wu, Wd, cfg.T, Y=Y, G_save=G, U_save=U, workspace=ws_f)
+        lb.lory_merged_ffn_bwd(X, w, Wg, Wu, Wd, dY, cfg.T, G_save=G, U_save=U, dX=dX, dWg=dWg, dWu=dWu,
+                               dWd=dWd, dw=dw, grad_dtype=gdt, workspace=ws_b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    tokens_per_s = cfg.tokens * args.steps / elapsed
+
+    # Same steps again with the library's event timing on: per-kernel-class durations.
+    lb.lory_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    stats = lb.lory_profile_read()
+    lb.lory_profile_enable(False)
+
+    kernels = {}
+    for s in stats:
+        n = max(s["launches"], 1)
+        kernels[s["name"]] = {
+            "launches_per_step": s["launches"] / args.steps,
+            "ms_per_step": s["ms"] / args.steps,
+            "avg_us": 1e3 * s["ms"] / n,
+            "tflops": (s["flops"] / (s["ms"] * 1e-3) / 1e12) if s["ms"] > 0 else 0.0,
+            "gbs": (s["bytes"] / (s["ms"] * 1e-3) / 1e9) if s["ms"] > 0 else 0.0,
+            "flops_per_launch": s["flops"] / n,
+            "bytes_per_launch": s["bytes"] / n,
+        }
+    dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"]) if kernels else None
+    roofline = None
+    if dominant:
+        kd = kernels[dominant]
+        if dominant.startswith("gemm"):
+            roofline = {"kernel": dominant, "bound": "mfma", "achieved": kd["tflops"], "peak": PEAK_BF16_TFLOPS,
+                        "unit": "TFLOP/s", "frac": kd["tflops"] / PEAK_BF16_TFLOPS}
+        else:
+            roofline = {"kernel": dominant, "bound": "hbm", "achieved": kd["gbs"], "peak": PEAK_HBM_GBS,
+                        "unit": "GB/s", "frac": kd["gbs"] / PEAK_HBM_GBS}
+        roofline["avg_launch_us"] = kd["avg_us"]
+        roofline["traffic"] = TRAFFIC_BYTES.get((args.config, dominant))
+
+    gemm_tflops = cfg.gemm_flops(True) / (ms_per_step * 1e-3) / 1e12
+    all_tflops = (cfg.gemm_flops(True) + cfg.merge_flops(4)) / (ms_per_step * 1e-3) / 1e12
+    out = {
+        "metric": "merged-MoE-FFN tokens/sec/GPU (fwd+bwd) + % bf16 MFMA peak",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B} L={cfg.L} T={cfg.T} d={cfg.d} d_ff={cfg.d_ff} E={cfg.E} "
+                               f"{cfg.dtype} route+fwd+bwd, grad_dtype={args.grad_dtype}, "
+                               f"save_GU={not args.no_save}",
+                   "tokens": cfg.tokens, "segments": cfg.S},
+        "gemm_tflops": gemm_tflops,
+        "pct_bf16_mfma_peak_gemm_only": 100.0 * gemm_tflops / PEAK_BF16_TFLOPS,
+        "pct_bf16_mfma_peak_with_merge": 100.0 * all_tflops / PEAK_BF16_TFLOPS,
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.verbose)
+    else:
+        out["cpu_baseline"] = None
+    if args.verbose:
+        for k, v in kernels.items():
+            print(f"[kernel] {k:18s} {v['launches_per_step']:6.1f} launches/step {v['ms_per_step']:8.3f} ms/step "
+                  f"avg {v['avg_us']:8.1f} us  {v['tflops']:8.1f} TFLOP/s {v['gbs']:8.0f} GB/s", file=sys.stderr)
+        print(f"[bench] {ms_per_step:.3f} ms/step, {tokens_per_s / 1e6:.3f} Mtok/s, GEMM {gemm_tflops:.0f} TFLOP/s",
+              file=sys.stderr)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

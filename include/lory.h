@@ -78,6 +78,27 @@ const char *lory_version(void);
 int lory_set_slab_budget(size_t bytes);
 
 /*
+ * Optional timing of the hot path's kernels, by class, with HIP events on the
+ * caller's stream (the measurement model is the paper's Appendix B: GEMM work
+ * 6*tokens*d*d_ff per pass direction, merge-class work 6*E*d*d_ff per segment
+ * and pass).  lory_profile_enable(1) makes every later launch record a pair
+ * of events tagged with that launch's algorithmic FLOPs and bytes;
+ * lory_profile_read waits for the recorded events, sums them per class into
+ * out[0..*n_out) (at most max_out entries; classes without launches are
+ * skipped) and clears the records.  Host-side state is process-global and not
+ * thread-safe; event objects are created on demand and reused.
+ */
+typedef struct {
+    char name[32];   /* kernel class, e.g. "gemm_gate_up", "merge", "scatter_dots" */
+    int32_t launches;
+    double ms;       /* summed event time of the launches */
+    double flops;    /* summed algorithmic floating-point operations */
+    double bytes;    /* summed algorithmic HBM bytes (reads + writes) */
+} lory_kernel_stat;
+int lory_profile_enable(int on);
+int lory_profile_read(lory_kernel_stat *out, int max_out, int *n_out);
+
+/*
  * Bytes of device workspace that lory_merged_ffn_fwd (pass = LORY_PASS_FWD)
  * or lory_merged_ffn_bwd (pass = LORY_PASS_BWD) needs for this shape.  The
  * workspace holds only transient data (merged-weight slabs, per-segment

@@ -24,7 +24,8 @@ LORY_ERR_NULL, LORY_ERR_SHAPE, LORY_ERR_DTYPE, LORY_ERR_ALIGN, LORY_ERR_WORKSPAC
 LORY_F32, LORY_BF16 = 0, 1
 LORY_PASS_FWD, LORY_PASS_BWD = 0, 1
 
-EXPORTS = ("lory_status_string", "lory_version", "lory_set_slab_budget", "lory_workspace_bytes", "lory_route",
+EXPORTS = ("lory_status_string", "lory_version", "lory_set_slab_budget", "lory_profile_enable",
+           "lory_profile_read", "lory_workspace_bytes", "lory_route",
            "lory_merged_ffn_fwd", "lory_merged_ffn_bwd")
 
 
@@ -32,6 +33,11 @@ class LoryShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("L", ctypes.c_int32), ("T", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("E", ctypes.c_int32),
                 ("dtype", ctypes.c_int32)]
+
+
+class LoryKernelStat(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 32), ("launches", ctypes.c_int32), ("ms", ctypes.c_double),
+                ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
 
 
 class LoryError(RuntimeError):
@@ -58,6 +64,10 @@ def lib() -> ctypes.CDLL:
         L.lory_version.restype = ctypes.c_char_p
         L.lory_set_slab_budget.argtypes = [sz]
         L.lory_set_slab_budget.restype = ci
+        L.lory_profile_enable.argtypes = [ci]
+        L.lory_profile_enable.restype = ci
+        L.lory_profile_read.argtypes = [ctypes.POINTER(LoryKernelStat), ci, ctypes.POINTER(ci)]
+        L.lory_profile_read.restype = ci
         L.lory_workspace_bytes.argtypes = [sp, ci, ctypes.POINTER(sz)]
         L.lory_workspace_bytes.restype = ci
         L.lory_route.argtypes = [sp, vp, vp, vp, vp, vp]
@@ -112,6 +122,19 @@ def _check(status: int, where: str) -> None:
 
 def lory_set_slab_budget(nbytes: int) -> None:
     _check(lib().lory_set_slab_budget(int(nbytes)), "lory_set_slab_budget")
+
+
+def lory_profile_enable(on: bool) -> None:
+    _check(lib().lory_profile_enable(int(bool(on))), "lory_profile_enable")
+
+
+def lory_profile_read() -> list:
+    """Per kernel class: dict(name, launches, ms, flops, bytes) since the last read."""
+    buf = (LoryKernelStat * 16)()
+    n = ctypes.c_int(0)
+    _check(lib().lory_profile_read(buf, 16, ctypes.byref(n)), "lory_profile_read")
+    return [dict(name=buf[i].name.decode(), launches=buf[i].launches, ms=buf[i].ms, flops=buf[i].flops,
+                 bytes=buf[i].bytes) for i in range(n.value)]
 
 
 def lory_workspace_bytes(shape: LoryShape, which_pass: int) -> int:

@@ -5,18 +5,27 @@ namespace lory {
 namespace k {
 
 namespace {
-// dw[s][e] = sum over slots of partials[slot][s][e], in slot order.
-__global__ void dw_reduce_kernel(const float *__restrict__ partials, int slots, int rows, int cols,
-                                 float *__restrict__ dw, int S, int E)
+// dw[s][e] = sum over slots of partials[slot][s][e].  One workgroup per segment row: thread
+// (e, g) adds slots g, g+16, ... in order, then the 16 group sums are added in order.
+__global__ __launch_bounds__(1024) void dw_reduce_kernel(const float *__restrict__ partials, int slots,
+                                                         int rows, int cols, float *__restrict__ dw,
+                                                         int S, int E)
 {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= S * E) return;
-    const int s = idx / E, e = idx % E;
+    __shared__ float red[16][64];
+    const int s = blockIdx.x;
+    const int e = threadIdx.x & 63, g = threadIdx.x >> 6;
     float acc = 0.f;
-    for (int k = 0; k < slots; ++k) acc += partials[((size_t)k * rows + s) * cols + e];
-    dw[idx] = acc;
+    if (e < E)
+        for (int k = g; k < slots; k += 16) acc += partials[((size_t)k * rows + s) * cols + e];
+    red[g][e] = acc;
+    __syncthreads();
+    if (g == 0 && e < E) {
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sum += red[i][e];
+        dw[(size_t)s * E + e] = sum;
+    }
 }
-
 
 constexpr int kMsGrid = 1024;  // workgroups; 4 wavefronts each stride over the 256-element units
 
@@ -25,13 +34,20 @@ int units_of(const ms::Rect &rc) { return ((rc.nr * rc.nc / 8) + 31) / 32; }
 
 int scatter_grid() { return kMsGrid; }
 
+namespace {
+int kbm_of(int S)
+{
+    const int KB = (S + 15) / 16;
+    int kbm = 1;
+    while (kbm < KB) kbm *= 2;
+    return kbm;
+}
+}  // namespace
+
 void scatter_partial_dims(int S, int E, int *rows, int *cols)
 {
-    const int SB = (S + 31) / 32, EB = (E + 31) / 32;
-    int nacc = 1;
-    while (nacc < SB * EB) nacc *= 2;
-    *rows = (nacc / EB) * 32;
-    *cols = EB * 32;
+    *rows = kbm_of(S) * 16;
+    *cols = ((E + 31) / 32) * 32;
 }
 
 hipError_t launch_merge(hipStream_t st, const ms::MergeParams &p)
@@ -54,26 +70,26 @@ hipError_t launch_merge(hipStream_t st, const ms::MergeParams &p)
 
 hipError_t launch_scatter(hipStream_t st, const ms::ScatterParams &p, int grid)
 {
-    const int SB = (p.S + 31) / 32, EB = (p.E + 31) / 32, KB = (p.S + 15) / 16;
-    const size_t lds = (size_t)EB * KB * 2 * 64 * 16;
-    if (lds > 64 * 1024 || SB * EB > 8 || EB > 2) return hipErrorInvalidValue;
-    int nacc = 1;
-    while (nacc < SB * EB) nacc *= 2;
-#define LORY_SCATTER(N, B) hipLaunchKernelGGL((ms::scatter_kernel<N, B>), dim3(grid), dim3(256), lds, st, p)
-    if (EB == 1) {
-        switch (nacc) {
-        case 1: LORY_SCATTER(1, 1); break;
-        case 2: LORY_SCATTER(2, 1); break;
-        case 4: LORY_SCATTER(4, 1); break;
-        default: LORY_SCATTER(8, 1); break;
-        }
-    } else {
-        switch (nacc) {
-        case 2: LORY_SCATTER(2, 2); break;
-        case 4: LORY_SCATTER(4, 2); break;
-        default: LORY_SCATTER(8, 2); break;
-        }
+    const int KB = (p.S + 15) / 16;
+    if (KB > 16 || p.e0 % 32 != 0 || p.e0 >= p.E) return hipErrorInvalidValue;
+    const int win = (p.E - p.e0 < 32) ? (p.E - p.e0) : 32;
+    const int eb16 = (win + 15) / 16;
+    const size_t lds = (size_t)KB * 2 * 64 * 16 + 4 * 16 * ms::kDotPitch;
+#define LORY_SCATTER(K, B) hipLaunchKernelGGL((ms::scatter_kernel<K, B>), dim3(grid), dim3(256), lds, st, p)
+#define LORY_SCATTER_K(B)                          \
+    switch (kbm_of(p.S)) {                         \
+    case 1: LORY_SCATTER(1, B); break;             \
+    case 2: LORY_SCATTER(2, B); break;             \
+    case 4: LORY_SCATTER(4, B); break;             \
+    case 8: LORY_SCATTER(8, B); break;             \
+    default: LORY_SCATTER(16, B); break;           \
     }
+    if (eb16 == 1) {
+        LORY_SCATTER_K(1)
+    } else {
+        LORY_SCATTER_K(2)
+    }
+#undef LORY_SCATTER_K
 #undef LORY_SCATTER
     return hipGetLastError();
 }
@@ -81,9 +97,8 @@ hipError_t launch_scatter(hipStream_t st, const ms::ScatterParams &p, int grid)
 hipError_t launch_dw_reduce(hipStream_t st, const float *partials, int slots, int rows, int cols,
                             float *dw, int S, int E)
 {
-    const int n = S * E;
-    hipLaunchKernelGGL(dw_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, st, partials, slots,
-                       rows, cols, dw, S, E);
+    hipLaunchKernelGGL(dw_reduce_kernel, dim3(S), dim3(1024), 0, st, partials, slots, rows, cols, dw, S,
+                       E);
     return hipGetLastError();
 }
 

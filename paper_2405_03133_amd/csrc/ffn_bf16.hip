@@ -69,10 +69,10 @@ struct Plan {
 Plan make_plan(const Dims &m)
 {
     Plan p;
-    const int cap = (m.E <= 32) ? 256 : 128;
+    const int cap = (m.E <= 32) ? 256 : 128;  // routing-weight operand tables of the merge kernel (LDS)
     p.Sc = m.S < cap ? m.S : cap;
-    p.gran_f = (m.dff % 128 == 0) ? 128 : 64;
-    p.gran_d = (m.d % 128 == 0) ? 128 : 64;
+    p.gran_f = (m.dff % 256 == 0) ? 256 : (m.dff % 128 == 0) ? 128 : 64;
+    p.gran_d = (m.d % 256 == 0) ? 256 : (m.d % 128 == 0) ? 128 : 64;
     const size_t budget = slab_budget_bytes();
     const size_t S = (size_t)p.Sc;
     p.nf_fwd = block_width(budget, S * m.d * 2 * 2, m.dff, p.gran_f);
@@ -109,8 +109,15 @@ Rect rect(long D, int pitch, int r0, int nr, int c0, int nc)
     return rc;
 }
 
+double gemm_flops(const Params &p, int nset, int nsrc)
+{
+    return 2.0 * p.batches * p.M * p.N * p.K * nset * nsrc;
+}
+
 hipError_t merge(hipStream_t st, const float *w, int S, int E, const bf *stack, const Rect &rc, bf *slab)
 {
+    const double n = (double)rc.nr * rc.nc;
+    prof::Range r(st, prof::kMerge, 2.0 * S * E * n, 2.0 * n * (E + S));
     MergeParams p;
     p.w = w;
     p.S = S;
@@ -137,6 +144,9 @@ hipError_t gate_up_block(hipStream_t st, const Dims &m, int S, const bf *X, cons
     p.B[1] = su; p.b_batch[1] = (long)m.d * nf; p.ldb[1] = nf;
     p.M = m.T; p.N = nf; p.K = m.d; p.batches = S;
     EpiGU epi = {G, U, Act, m.T, m.dff, n0};
+    const double out_elems = (double)S * m.T * nf * ((G ? 2 : 0) + (Act ? 1 : 0));
+    prof::Range r(st, prof::kGemmGU, gemm_flops(p, 2, 1),
+                  2.0 * ((double)S * m.T * m.d + 2.0 * S * m.d * nf + out_elems));
     return k::launch_gu(st, p, epi);
 }
 
@@ -187,6 +197,8 @@ int bf16_ffn_fwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
             p.B[0] = slab; p.b_batch[0] = (long)m.dff * jf; p.ldb[0] = jf;
             p.M = m.T; p.N = jf; p.K = m.dff; p.batches = S;
             EpiStore epi = {Y + (size_t)s0 * TD + j0, TD, m.d};
+            prof::Range r(st, prof::kGemmDown, gemm_flops(p, 1, 1),
+                          2.0 * ((double)S * TF + (double)S * m.dff * jf + (double)S * m.T * jf));
             LORY_TRY(k::launch_down(st, p, epi));
         }
     }
@@ -251,6 +263,8 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
                 p.B[0] = s_md; p.b_batch[0] = (long)nf * m.d; p.ldb[0] = m.d;
                 p.M = m.T; p.N = nf; p.K = m.d; p.batches = S;
                 EpiDA epi = {Gc, Uc, dG, dU, Act, m.T, m.dff, n0};
+                prof::Range r(st, prof::kGemmDA, gemm_flops(p, 1, 1),
+                              2.0 * ((double)S * TD + (double)S * nf * m.d + 5.0 * S * m.T * nf));
                 LORY_TRY(k::launch_da(st, p, epi));
             }
             // dWd_bar rows = A^T dY
@@ -260,6 +274,8 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
                 p.B[0] = dYc; p.b_batch[0] = TD; p.ldb[0] = m.d;
                 p.M = nf; p.N = m.d; p.K = m.T; p.batches = S;
                 EpiStore epi = {s_gd, (long)nf * m.d, m.d};
+                prof::Range r(st, prof::kGemmDWD, gemm_flops(p, 1, 1),
+                              2.0 * ((double)S * m.T * nf + (double)S * TD + (double)S * nf * m.d));
                 LORY_TRY(k::launch_dwd(st, p, epi));
             }
             // dWg_bar, dWu_bar columns = X^T dG, X^T dU
@@ -270,6 +286,8 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
                 p.B[1] = dU + n0; p.b_batch[1] = TF; p.ldb[1] = m.dff;
                 p.M = m.d; p.N = nf; p.K = m.T; p.batches = S;
                 EpiStore2 epi = {s_gg, s_gu, (long)m.d * nf, nf};
+                prof::Range r(st, prof::kGemmDWGU, gemm_flops(p, 2, 1),
+                              2.0 * ((double)S * TD + 2.0 * S * m.T * nf + 2.0 * S * m.d * nf));
                 LORY_TRY(k::launch_dwgu(st, p, epi));
             }
             // E-way scatter and router-weight inner products
@@ -278,13 +296,21 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
             const bf *gsl[3] = {s_gd, s_gg, s_gu};
             const Rect rcs[3] = {rows_d, cols_f, cols_f};
             for (int i = 0; i < 3; ++i) {
-                ScatterParams sp;
-                sp.w = wc; sp.S = S; sp.E = m.E;
-                sp.gslab = gsl[i]; sp.seg_stride = (long)rcs[i].nr * rcs[i].nc;
-                sp.stack = stacks[i]; sp.dW = grads[i]; sp.rc = rcs[i];
-                sp.grad_f32 = grad_f32; sp.accumulate = acc_dW;
-                sp.partials = partials; sp.partials_add = partials_add;
-                LORY_TRY(k::launch_scatter(st, sp, grid));
+                const int padd = partials_add;
+                for (int e0 = 0; e0 < m.E; e0 += 32) {  // windows of 32 experts
+                    ScatterParams sp;
+                    sp.w = wc; sp.S = S; sp.E = m.E; sp.e0 = e0;
+                    sp.gslab = gsl[i]; sp.seg_stride = (long)rcs[i].nr * rcs[i].nc;
+                    sp.stack = stacks[i]; sp.dW = grads[i]; sp.rc = rcs[i];
+                    sp.grad_f32 = grad_f32; sp.accumulate = acc_dW;
+                    sp.partials = partials; sp.pcols = pl.pcol; sp.partials_add = padd;
+                    const int win = (m.E - e0 < 32) ? (m.E - e0) : 32;
+                    const double n = (double)rcs[i].nr * rcs[i].nc;
+                    const double gsz = grad_f32 ? 4.0 : 2.0;
+                    prof::Range r(st, prof::kScatter, 4.0 * S * win * n,
+                                  2.0 * n * (S + win) + gsz * n * win * (acc_dW ? 2 : 1));
+                    LORY_TRY(k::launch_scatter(st, sp, grid));
+                }
                 partials_add = 1;
             }
         }
@@ -304,11 +330,14 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
             p.B[1] = s_u; p.b_batch[1] = (long)kf * m.dff; p.ldb[1] = m.dff;
             p.M = m.T; p.N = kf; p.K = m.dff; p.batches = S;
             EpiStore epi = {dX + (size_t)s0 * TD + k0, TD, m.d};
+            prof::Range r(st, prof::kGemmDX, gemm_flops(p, 1, 2),
+                          2.0 * (2.0 * S * TF + 2.0 * S * kf * m.dff + (double)S * m.T * kf));
             LORY_TRY(k::launch_dx(st, p, epi));
         }
 
         int prow, pcol;
         k::scatter_partial_dims(S, m.E, &prow, &pcol);
+        prof::Range r(st, prof::kDwReduce, (double)grid * 4 * S * m.E, 4.0 * grid * 4 * prow * pcol);
         LORY_TRY(k::launch_dw_reduce(st, partials, grid * 4, prow, pcol, dw + (size_t)s0 * m.E, S, m.E));
     }
     return LORY_OK;

@@ -33,6 +33,7 @@ namespace gemm {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int BK = 64;
@@ -74,56 +75,58 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
     return (uint16_t)(u >> 16);
 }
 
-// ---- global -> register staging of one K step -------------------------------
+// ---- global -> register -> LDS staging of one K step --------------------------
+//
+// KC tile (ROWS rows of 64 bf16): thread t moves chunk (t & 7) of rows (t >> 3) + 32 i.
+// TR tile (64 K rows of WIDTH bf16): thread t moves chunks t + 256 i of the row-major tile.
 
-template <int ROWS>  // KC tile: ROWS rows of 64 bf16
-struct StageKC {
-    static constexpr int n = ROWS / 32;
-    uint4 v[n];
-    __device__ __forceinline__ void load(const uint16_t *base, int ld, int row0, int k0, int tid)
-    {
-        const int c = tid & 7;
+template <int ROWS>
+__device__ __forceinline__ void load_kc(u32x4 (&v)[ROWS / 32], const uint16_t *base, int ld, int row0,
+                                        int k0, int tid)
+{
+    const int c = tid & 7;
 #pragma unroll
-        for (int i = 0; i < n; ++i) {
-            const int row = (tid >> 3) + 32 * i;
-            v[i] = *reinterpret_cast<const uint4 *>(base + (size_t)(row0 + row) * ld + k0 + c * 8);
-        }
+    for (int i = 0; i < ROWS / 32; ++i) {
+        const int row = (tid >> 3) + 32 * i;
+        v[i] = *reinterpret_cast<const u32x4 *>(base + (size_t)(row0 + row) * ld + k0 + c * 8);
     }
-    __device__ __forceinline__ void store(char *lds, int tid) const
-    {
-        const int c = tid & 7;
-#pragma unroll
-        for (int i = 0; i < n; ++i) {
-            const int row = (tid >> 3) + 32 * i;
-            *reinterpret_cast<uint4 *>(lds + row * 128 + ((c ^ swz(row)) << 4)) = v[i];
-        }
-    }
-};
+}
 
-template <int WIDTH>  // MC / NC tile: 64 rows (K) of WIDTH bf16
-struct StageTR {
-    static constexpr int n = WIDTH / 32;
-    static constexpr int cpr = WIDTH / 8;  // 16-byte chunks per row
-    uint4 v[n];
-    __device__ __forceinline__ void load(const uint16_t *base, int ld, int col0, int k0, int tid)
-    {
+template <int ROWS>
+__device__ __forceinline__ void store_kc(const u32x4 (&v)[ROWS / 32], char *lds, int tid)
+{
+    const int c = tid & 7;
 #pragma unroll
-        for (int i = 0; i < n; ++i) {
-            const int idx = tid + kThreads * i;
-            const int row = idx / cpr, c = idx % cpr;
-            v[i] = *reinterpret_cast<const uint4 *>(base + (size_t)(k0 + row) * ld + col0 + c * 8);
-        }
+    for (int i = 0; i < ROWS / 32; ++i) {
+        const int row = (tid >> 3) + 32 * i;
+        *reinterpret_cast<u32x4 *>(lds + row * 128 + ((c ^ swz(row)) << 4)) = v[i];
     }
-    __device__ __forceinline__ void store(char *lds, int tid) const
-    {
+}
+
+template <int WIDTH>
+__device__ __forceinline__ void load_tr(u32x4 (&v)[WIDTH / 32], const uint16_t *base, int ld, int col0,
+                                        int k0, int tid)
+{
+    constexpr int cpr = WIDTH / 8;  // 16-byte chunks per row
 #pragma unroll
-        for (int i = 0; i < n; ++i) {
-            const int idx = tid + kThreads * i;
-            const int row = idx / cpr, c = idx % cpr;
-            *reinterpret_cast<uint4 *>(lds + row * tr_pitch(WIDTH) + (c << 4)) = v[i];
-        }
+    for (int i = 0; i < WIDTH / 32; ++i) {
+        const int idx = tid + kThreads * i;
+        const int row = idx / cpr, c = idx % cpr;
+        v[i] = *reinterpret_cast<const u32x4 *>(base + (size_t)(k0 + row) * ld + col0 + c * 8);
     }
-};
+}
+
+template <int WIDTH>
+__device__ __forceinline__ void store_tr(const u32x4 (&v)[WIDTH / 32], char *lds, int tid)
+{
+    constexpr int cpr = WIDTH / 8;
+#pragma unroll
+    for (int i = 0; i < WIDTH / 32; ++i) {
+        const int idx = tid + kThreads * i;
+        const int row = idx / cpr, c = idx % cpr;
+        *reinterpret_cast<u32x4 *>(lds + row * tr_pitch(WIDTH) + (c << 4)) = v[i];
+    }
+}
 
 // ---- LDS -> MFMA operand fragments ------------------------------------------
 
@@ -163,7 +166,7 @@ __device__ __forceinline__ bf16x8 frag_tr(const char *lds, int col0, int kk, int
 // Epi is a functor:  epi(batch, m, n, const float (&v)[NSET])  called once per
 // output element; consecutive lanes get consecutive n.
 template <int BM, int BN, int WAVES_M, int NSET, int NSRC, bool A_MC, bool B_NC, class Epi>
-__global__ __launch_bounds__(kThreads) void gemm_kernel(const Params p, const Epi epi)
+__global__ __launch_bounds__(kThreads, 1) void gemm_kernel(const Params p, const Epi epi)
 {
     static_assert(NSET == 1 || NSRC == 1, "either two operand sets or two sources");
     constexpr int WAVES_N = 4 / WAVES_M;
@@ -203,35 +206,52 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const Params p, const Ep
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[s][i][j][r] = 0.f;
 
-    typename std::conditional<A_MC, StageTR<BM>, StageKC<BM>>::type sa;
-    typename std::conditional<B_NC, StageTR<BN>, StageKC<BN>>::type sb[NSET];
+    u32x4 ra[BM / 32];
+    u32x4 rb[NSET][BN / 32];
 
-    auto load_tile = [&](int t) {
-        const int src = (NSRC == 2) ? (t / ktiles) : 0;
-        const int k0 = (t % ktiles) * BK;
-        const uint16_t *a = p.A[src] + (size_t)batch * p.a_batch[src];
-        sa.load(a, p.lda[src], m0, k0, tid);
-#pragma unroll
-        for (int s = 0; s < NSET; ++s) {
-            const int bi = (NSRC == 2) ? src : s;
-            const uint16_t *b = p.B[bi] + (size_t)batch * p.b_batch[bi];
-            sb[s].load(b, p.ldb[bi], n0, k0, tid);
-        }
-    };
-    auto store_tile = [&](int stage) {
-        char *base = smem + stage * SM::stage;
-        sa.store(base, tid);
-#pragma unroll
-        for (int s = 0; s < NSET; ++s) sb[s].store(base + SM::a_bytes + s * SM::b_bytes, tid);
-    };
+#define LORY_LOAD_TILE(t_)                                                                     \
+    do {                                                                                       \
+        const int src_ = (NSRC == 2) ? ((t_) / ktiles) : 0;                                    \
+        const int k0_ = ((t_) % ktiles) * BK;                                                  \
+        const uint16_t *a_ = p.A[src_] + (size_t)batch * p.a_batch[src_];                      \
+        if constexpr (A_MC)                                                                    \
+            load_tr<BM>(ra, a_, p.lda[src_], m0, k0_, tid);                                    \
+        else                                                                                   \
+            load_kc<BM>(ra, a_, p.lda[src_], m0, k0_, tid);                                    \
+        _Pragma("unroll") for (int s_ = 0; s_ < NSET; ++s_)                                    \
+        {                                                                                      \
+            const int bi_ = (NSRC == 2) ? src_ : s_;                                           \
+            const uint16_t *b_ = p.B[bi_] + (size_t)batch * p.b_batch[bi_];                    \
+            if constexpr (B_NC)                                                                \
+                load_tr<BN>(rb[s_], b_, p.ldb[bi_], n0, k0_, tid);                             \
+            else                                                                               \
+                load_kc<BN>(rb[s_], b_, p.ldb[bi_], n0, k0_, tid);                             \
+        }                                                                                      \
+    } while (0)
 
-    load_tile(0);
-    store_tile(0);
+#define LORY_STORE_TILE(stage_)                                                                \
+    do {                                                                                       \
+        char *base_ = smem + (stage_) * SM::stage;                                             \
+        if constexpr (A_MC)                                                                    \
+            store_tr<BM>(ra, base_, tid);                                                      \
+        else                                                                                   \
+            store_kc<BM>(ra, base_, tid);                                                      \
+        _Pragma("unroll") for (int s_ = 0; s_ < NSET; ++s_)                                    \
+        {                                                                                      \
+            if constexpr (B_NC)                                                                \
+                store_tr<BN>(rb[s_], base_ + SM::a_bytes + s_ * SM::b_bytes, tid);             \
+            else                                                                               \
+                store_kc<BN>(rb[s_], base_ + SM::a_bytes + s_ * SM::b_bytes, tid);             \
+        }                                                                                      \
+    } while (0)
+
+    LORY_LOAD_TILE(0);
+    LORY_STORE_TILE(0);
     __syncthreads();
 
     for (int t = 0; t < total_tiles; ++t) {
         const bool more = (t + 1 < total_tiles);
-        if (more) load_tile(t + 1);
+        if (more) LORY_LOAD_TILE(t + 1);
         const char *base = smem + (t & 1) * SM::stage;
         const char *la = base;
         const char *lb = base + SM::a_bytes;
@@ -264,9 +284,11 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const Params p, const Ep
                         acc[s][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[s][j],
                                                                                acc[s][i][j], 0, 0, 0);
         }
-        if (more) store_tile((t + 1) & 1);
+        if (more) LORY_STORE_TILE((t + 1) & 1);
         __syncthreads();
     }
+#undef LORY_LOAD_TILE
+#undef LORY_STORE_TILE
 
     // accumulator element r of a 32x32 block: row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
 #pragma unroll

@@ -47,6 +47,15 @@ const char *lory_version(void) { return "0.1"; }
 
 int lory_set_slab_budget(size_t bytes) { return lory::set_slab_budget(bytes); }
 
+int lory_profile_enable(int on) { return lory::prof::set_enabled(on); }
+
+int lory_profile_read(lory_kernel_stat *out, int max_out, int *n_out)
+{
+    if (!out || !n_out) return LORY_ERR_NULL;
+    if (max_out <= 0) return LORY_ERR_SHAPE;
+    return lory::prof::read(out, max_out, n_out);
+}
+
 int lory_workspace_bytes(const lory_shape *shape, int pass, size_t *bytes_out)
 {
     if (!bytes_out) return LORY_ERR_NULL;
@@ -68,6 +77,9 @@ int lory_route(const lory_shape *shape, const void *X, const void *R, float *w, 
     if (!X || !R || !w) return LORY_ERR_NULL;
     if (!aligned16(X) || !aligned16(R) || !aligned16(w) || !aligned16(hbar_opt)) return LORY_ERR_ALIGN;
     const Dims m = lory::make_dims(*shape);
+    const double esz = (m.dtype == LORY_F32) ? 4.0 : 2.0;
+    lory::prof::Range r((hipStream_t)stream, lory::prof::kRoute, 2.0 * m.S * m.d * m.E + (double)m.tokens * m.d,
+                        esz * ((double)m.tokens * m.d + (double)m.d * m.E) + 4.0 * m.S * m.E);
     return lory::route_launch(m, X, R, w, hbar_opt, nullptr, (hipStream_t)stream);
 }
 

@@ -40,6 +40,26 @@ inline int launch_status()
     return hipGetLastError() == hipSuccess ? LORY_OK : LORY_ERR_DEVICE;
 }
 
+// ---- optional event timing per kernel class (profile.hip)
+namespace prof {
+enum Class { kRoute = 0, kMerge, kGemmGU, kGemmDown, kGemmDA, kGemmDX, kGemmDWGU, kGemmDWD, kScatter,
+             kDwReduce, kNumClasses };
+bool enabled();
+int set_enabled(int on);
+int read(lory_kernel_stat *out, int max_out, int *n_out);
+// Brackets the launches issued during its lifetime with two events (only when enabled).
+class Range {
+public:
+    Range(hipStream_t st, int cls, double flops, double bytes);
+    ~Range();
+    Range(const Range &) = delete;
+    Range &operator=(const Range &) = delete;
+private:
+    hipStream_t st_;
+    int idx_;
+};
+}  // namespace prof
+
 // ---- routing (route.hip)
 int route_launch(const Dims &m, const void *X, const void *R, float *w, float *hbar,
                  float *hbar_scratch, hipStream_t st);

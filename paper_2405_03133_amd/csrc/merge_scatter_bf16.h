@@ -196,6 +196,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeParams p)
 struct ScatterParams {
     const float *w;          // [S, E]
     int S, E;
+    int e0;                  // first expert of the window of up to 32 experts this launch handles
     const uint16_t *gslab;   // per-segment weight gradients [S][nr*nc] (bf16)
     long seg_stride;
     const uint16_t *stack;   // expert stack base of this matrix (for the inner products)
@@ -203,176 +204,204 @@ struct ScatterParams {
     Rect rc;
     int grad_f32;            // dW is fp32 (else bf16)
     int accumulate;          // add to dW instead of overwriting it
-    float *partials;         // [gridDim.x * 4][SB*32][EB*32] per-wave router-weight partial sums
+    float *partials;         // [gridDim.x * 4][KBM*16][pcols] per-wave router-weight partial sums
+    int pcols;               // columns of a partials row (>= E)
     int partials_add;        // add to the existing partials instead of overwriting them
 };
 
-// NACC = SBn * EBS 32x32 router-weight accumulator blocks, SBn >= ceil(S/32),
-// EBS >= ceil(E/32).  grid.x workgroups of 256 threads stride over the units.
-// Dynamic LDS: ceil(E/32) * ceil(S/16) * 2 * 64 * 16 bytes (transposed
-// routing-weight operands).
-template <int NACC, int EBS>
-__global__ __launch_bounds__(256) void scatter_kernel(const ScatterParams p)
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kDotPitch = 528;  // bytes per segment row of a wave's LDS staging area (512 + 16)
+
+// One launch handles the experts e0 .. e0+31 (clipped to E).
+//   KBM  >= ceil(S / 16): static bound on the 16-segment K blocks
+//   EB16 =  ceil(window / 16): 16-expert blocks of the router-weight accumulators (1 or 2)
+// Per unit of 32 chunks a wave
+//   (1) loads the window's expert tiles once (B operand of the inner products),
+//   (2) walks the segments 16 at a time: loads their gradient chunks, parks them in its own LDS
+//       area, transposes them in registers and feeds the scatter MFMAs (K = segments), then
+//       re-reads them from LDS in the row-per-lane layout the inner-product MFMAs want
+//       (16x16x32, K = elements), so every gradient byte is fetched from memory once.
+// Dynamic LDS: KB * 2 * 64 * 16 bytes of routing-weight operands + 4 * 16 * kDotPitch.
+template <int KBM, int EB16>
+__global__ __launch_bounds__(256, 1) void scatter_kernel(const ScatterParams p)
 {
-    constexpr int SBn = NACC / EBS;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    uint4 *wtab = reinterpret_cast<uint4 *>(smem);  // [eb][kb][hi/lo][lane]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 31, h = lane >> 5;
-    const int EB = (p.E + 31) >> 5, KB = (p.S + 15) >> 4;
+    const int KB = (p.S + 15) >> 4;
+    uint4 *wtab = reinterpret_cast<uint4 *>(smem);  // [kb][hi/lo][lane]
+    char *park = smem + (size_t)KB * 2 * 64 * 16 + wave * (16 * kDotPitch);
+    const int Ewin = (p.E - p.e0 < 32) ? (p.E - p.e0) : 32;
 
-    for (int idx = tid; idx < EB * KB * 64; idx += 256) {
-        const int l = idx & 63, kb = (idx >> 6) % KB, eb = (idx >> 6) / KB;
-        const int e = eb * 32 + (l & 31);
+    for (int idx = tid; idx < KB * 64; idx += 256) {
+        const int l = idx & 63, kb = idx >> 6;
+        const int e = l & 31;
         float v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int seg = 16 * kb + 8 * (l >> 5) + i;
-            v[i] = (seg < p.S && e < p.E) ? p.w[(size_t)seg * p.E + e] : 0.f;
+            v[i] = (seg < p.S && e < Ewin) ? p.w[(size_t)seg * p.E + p.e0 + e] : 0.f;
         }
         Frag hi, lo;
         split_hi_lo(v, hi, lo);
-        wtab[((eb * KB + kb) * 2 + 0) * 64 + l] = hi.u;
-        wtab[((eb * KB + kb) * 2 + 1) * 64 + l] = lo.u;
+        wtab[(kb * 2 + 0) * 64 + l] = hi.u;
+        wtab[(kb * 2 + 1) * 64 + l] = lo.u;
     }
     __syncthreads();
 
     const int Q = (p.rc.nr * p.rc.nc) >> 3;
     const int units = (Q + 31) >> 5;
     const int stride = gridDim.x * 4;
+    const uint16_t *stack = p.stack + (size_t)p.e0 * p.rc.expert_stride;
 
-    f32x16 dots[NACC];
+    f32x4 dots[KBM][EB16];
 #pragma unroll
-    for (int a = 0; a < NACC; ++a)
+    for (int a = 0; a < KBM; ++a)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) dots[a][r] = 0.f;
+        for (int b = 0; b < EB16; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dots[a][b][r] = 0.f;
 
     for (int unit = blockIdx.x * 4 + wave; unit < units; unit += stride) {
         const int q = unit * 32 + ln;
         const bool ok = q < Q;
 
-        // ---- dW[e] = sum_s w[s,e] * gslab[s]   (K = segments, 16 per step)
-        f32x16 acc[EBS][8];
+        // expert tiles of the window: lane (n = lane & 15, chunk group = lane >> 4)
+        Frag Bst[EB16][8];
 #pragma unroll
-        for (int eb = 0; eb < EBS; ++eb)
+        for (int kq = 0; kq < 8; ++kq) {
+            const int qq = unit * 32 + 4 * kq + (lane >> 4);
+            const bool okq = qq < Q;
+            const long off2 = okq ? rect_offset(p.rc, qq) : 0;
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[eb][j][r] = 0.f;
-        for (int kb = 0; kb < KB; ++kb) {
-            Frag Rg[8], P[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int seg = 16 * kb + 8 * h + i;
-                if (ok && seg < p.S)
-                    Rg[i].u = *reinterpret_cast<const uint4 *>(p.gslab + (size_t)seg * p.seg_stride + (size_t)q * 8);
+            for (int b = 0; b < EB16; ++b) {
+                const int e = b * 16 + (lane & 15);
+                if (okq && e < Ewin)
+                    Bst[b][kq].u = *reinterpret_cast<const uint4 *>(stack + (size_t)e * p.rc.expert_stride + off2);
                 else
-                    Rg[i].u = make_uint4(0, 0, 0, 0);
-            }
-            transpose8x8(Rg, P);
-#pragma unroll
-            for (int eb = 0; eb < EBS; ++eb) {
-                if (eb < EB) {
-                    Frag whi, wlo;
-                    whi.u = wtab[((eb * KB + kb) * 2 + 0) * 64 + lane];
-                    wlo.u = wtab[((eb * KB + kb) * 2 + 1) * 64 + lane];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        acc[eb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(whi.v, P[j].v, acc[eb][j], 0, 0, 0);
-                        acc[eb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wlo.v, P[j].v, acc[eb][j], 0, 0, 0);
-                    }
-                }
+                    Bst[b][kq].u = make_uint4(0, 0, 0, 0);
             }
         }
+
+        f32x16 acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+        Frag Rg[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int seg = 8 * h + i;
+            if (ok && seg < p.S)
+                Rg[i].u = *reinterpret_cast<const uint4 *>(p.gslab + (size_t)seg * p.seg_stride + (size_t)q * 8);
+            else
+                Rg[i].u = make_uint4(0, 0, 0, 0);
+        }
+
+#pragma unroll
+        for (int kb = 0; kb < KBM; ++kb) {
+            if (kb < KB) {
+                Frag P[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    *reinterpret_cast<uint4 *>(park + (8 * h + i) * kDotPitch + ln * 16) = Rg[i].u;
+                transpose8x8(Rg, P);
+                if (kb + 1 < KB) {  // next 16 segments, in flight behind the MFMAs
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int seg = 16 * (kb + 1) + 8 * h + i;
+                        if (ok && seg < p.S)
+                            Rg[i].u = *reinterpret_cast<const uint4 *>(p.gslab + (size_t)seg * p.seg_stride +
+                                                                       (size_t)q * 8);
+                        else
+                            Rg[i].u = make_uint4(0, 0, 0, 0);
+                    }
+                }
+                Frag whi, wlo;
+                whi.u = wtab[(kb * 2 + 0) * 64 + lane];
+                wlo.u = wtab[(kb * 2 + 1) * 64 + lane];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(whi.v, P[j].v, acc[j], 0, 0, 0);
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wlo.v, P[j].v, acc[j], 0, 0, 0);
+                }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int kq = 0; kq < 8; ++kq) {
+                    Frag af;
+                    af.u = *reinterpret_cast<const uint4 *>(park + (lane & 15) * kDotPitch +
+                                                            (4 * kq + (lane >> 4)) * 16);
+#pragma unroll
+                    for (int b = 0; b < EB16; ++b)
+                        dots[kb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af.v, Bst[b][kq].v, dots[kb][b],
+                                                                             0, 0, 0);
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+
         if (ok) {
             const long off = rect_offset(p.rc, q);
 #pragma unroll
-            for (int eb = 0; eb < EBS; ++eb)
+            for (int r = 0; r < 16; ++r) {
+                const int e = 8 * (r >> 2) + 4 * h + (r & 3);
+                if (e >= Ewin) continue;
+                float v[8];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int e = eb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                    if (e >= p.E) continue;
-                    float v[8];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) v[j] = acc[eb][j][r];
-                    if (p.grad_f32) {
-                        float4 *dst = reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.dW) +
-                                                                 (size_t)e * p.rc.expert_stride + off);
-                        float4 o0 = make_float4(v[0], v[1], v[2], v[3]);
-                        float4 o1 = make_float4(v[4], v[5], v[6], v[7]);
-                        if (p.accumulate) {
-                            const float4 c0 = dst[0], c1 = dst[1];
-                            o0.x += c0.x; o0.y += c0.y; o0.z += c0.z; o0.w += c0.w;
-                            o1.x += c1.x; o1.y += c1.y; o1.z += c1.z; o1.w += c1.w;
-                        }
-                        dst[0] = o0;
-                        dst[1] = o1;
-                    } else {
-                        uint4 *dst = reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.dW) +
-                                                               (size_t)e * p.rc.expert_stride + off);
-                        if (p.accumulate) {
-                            const uint4 c = *dst;
-                            const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                v[2 * i] += __uint_as_float(cw[i] << 16);
-                                v[2 * i + 1] += __uint_as_float(cw[i] & 0xffff0000u);
-                            }
-                        }
-                        uint4 o;
-                        o.x = pack_bf16(v[0], v[1]);
-                        o.y = pack_bf16(v[2], v[3]);
-                        o.z = pack_bf16(v[4], v[5]);
-                        o.w = pack_bf16(v[6], v[7]);
-                        *dst = o;
+                for (int j = 0; j < 8; ++j) v[j] = acc[j][r];
+                const size_t eoff = (size_t)(p.e0 + e) * p.rc.expert_stride + off;
+                if (p.grad_f32) {
+                    float4 *dst = reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.dW) + eoff);
+                    float4 o0 = make_float4(v[0], v[1], v[2], v[3]);
+                    float4 o1 = make_float4(v[4], v[5], v[6], v[7]);
+                    if (p.accumulate) {
+                        const float4 c0 = dst[0], c1 = dst[1];
+                        o0.x += c0.x; o0.y += c0.y; o0.z += c0.z; o0.w += c0.w;
+                        o1.x += c1.x; o1.y += c1.y; o1.z += c1.z; o1.w += c1.w;
                     }
+                    dst[0] = o0;
+                    dst[1] = o1;
+                } else {
+                    uint4 *dst = reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.dW) + eoff);
+                    if (p.accumulate) {
+                        const uint4 c = *dst;
+                        const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            v[2 * i] += __uint_as_float(cw[i] << 16);
+                            v[2 * i + 1] += __uint_as_float(cw[i] & 0xffff0000u);
+                        }
+                    }
+                    uint4 o;
+                    o.x = pack_bf16(v[0], v[1]);
+                    o.y = pack_bf16(v[2], v[3]);
+                    o.z = pack_bf16(v[4], v[5]);
+                    o.w = pack_bf16(v[6], v[7]);
+                    *dst = o;
                 }
-        }
-
-        // ---- dw[s,e] += <stack[e], gslab[s]> over this unit  (K = elements, 16 per step)
-        const int q0 = unit * 32;
-#pragma unroll 4
-        for (int ks = 0; ks < 16; ++ks) {
-            const int qq = q0 + 2 * ks + h;
-            const bool okq = qq < Q;
-            const long off2 = okq ? rect_offset(p.rc, qq) : 0;
-            Frag bfr[EBS];
-#pragma unroll
-            for (int eb = 0; eb < EBS; ++eb) {
-                const int e = eb * 32 + ln;
-                if (okq && e < p.E)
-                    bfr[eb].u = *reinterpret_cast<const uint4 *>(p.stack + (size_t)e * p.rc.expert_stride + off2);
-                else
-                    bfr[eb].u = make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int sb = 0; sb < SBn; ++sb) {
-                const int seg = sb * 32 + ln;
-                Frag af;
-                if (okq && seg < p.S)
-                    af.u = *reinterpret_cast<const uint4 *>(p.gslab + (size_t)seg * p.seg_stride + (size_t)qq * 8);
-                else
-                    af.u = make_uint4(0, 0, 0, 0);
-#pragma unroll
-                for (int eb = 0; eb < EBS; ++eb)
-                    dots[sb * EBS + eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bfr[eb].v,
-                                                                                dots[sb * EBS + eb], 0, 0, 0);
             }
         }
     }
 
-    // per-wave partial sums; a later kernel adds them up in slot order
+    // per-wave partial sums of dw; a later kernel adds them up in slot order.
+    // 16x16 accumulator element r: row (segment) 4*(lane>>4) + r, column (expert) lane & 15.
     const size_t slot = (size_t)blockIdx.x * 4 + wave;
-    float *part = p.partials + slot * (SBn * 32) * (EBS * 32);
+    float *part = p.partials + slot * (KBM * 16) * p.pcols;
 #pragma unroll
-    for (int a = 0; a < NACC; ++a)
+    for (int kb = 0; kb < KBM; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int seg = (a / EBS) * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-            const int e = (a % EBS) * 32 + ln;
-            float *dst = part + (size_t)seg * (EBS * 32) + e;
-            *dst = p.partials_add ? (*dst + dots[a][r]) : dots[a][r];
-        }
+        for (int b = 0; b < EB16; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int seg = kb * 16 + 4 * (lane >> 4) + r;
+                const int e = p.e0 + b * 16 + (lane & 15);
+                if (e < p.pcols) {
+                    float *dst = part + (size_t)seg * p.pcols + e;
+                    *dst = p.partials_add ? (*dst + dots[kb][b][r]) : dots[kb][b][r];
+                }
+            }
 }
 
 }  // namespace ms
