@@ -7,8 +7,19 @@ namespace k {
 
 hipError_t launch_dwgu(hipStream_t st, const gemm::Params &p, const EpiStore2 &e)
 {
-    // A = X_s stored [T][d] (M contiguous), B = dG_s / dU_s stored [T][d_ff] (N contiguous)
-    if (p.M % 256 == 0 && p.N % 128 == 0) return gemm::launch<256, 128, 2, 2, 1, true, true>(p, e, st);
+    // A = X_s stored [T][d] (M contiguous), B = dG_s / dU_s stored [T][d_ff] (N contiguous).
+    // The contraction is only T long, so the kernel is bound by writing its output; two
+    // single-set launches with square tiles and several workgroups per CU do better than one
+    // launch that shares X between the two operand sets.
+    if (p.N % 128 == 0 || p.N % 64 != 0) {
+        gemm::Params q = p;
+        EpiStore e0 = {e.C0, e.c_batch, e.ldc};
+        hipError_t rc = launch_dwd(st, q, e0);
+        if (rc != hipSuccess) return rc;
+        q.B[0] = p.B[1]; q.b_batch[0] = p.b_batch[1]; q.ldb[0] = p.ldb[1];
+        EpiStore e1 = {e.C1, e.c_batch, e.ldc};
+        return launch_dwd(st, q, e1);
+    }
     if (p.M % 128 == 0) return gemm::launch<128, 64, 2, 2, 1, true, true>(p, e, st);
     return gemm::launch<64, 64, 2, 2, 1, true, true>(p, e, st);
 }
@@ -16,7 +27,6 @@ hipError_t launch_dwgu(hipStream_t st, const gemm::Params &p, const EpiStore2 &e
 hipError_t launch_dwd(hipStream_t st, const gemm::Params &p, const EpiStore &e)
 {
     // A = Act_s stored [T][d_ff] (M contiguous), B = dY_s stored [T][d] (N contiguous)
-    if (p.N % 256 == 0 && p.M % 256 == 0) return gemm::launch<256, 256, 2, 1, 1, true, true>(p, e, st);
     if (p.N % 128 == 0) {
         if (p.M % 128 == 0) return gemm::launch<128, 128, 2, 1, 1, true, true>(p, e, st);
         return gemm::launch<64, 128, 2, 1, 1, true, true>(p, e, st);

@@ -11,60 +11,131 @@ namespace k {
 using gemm::bf16_bits_to_float;
 using gemm::float_to_bf16_bits;
 
-// G, U (optional) and A = silu(G) * U of one column block of d_ff.
+using gemm::u32x2;
+
+struct NoIn {};
+
+__device__ __forceinline__ u32x2 pack4(float a, float b, float c, float d)
+{
+    u32x2 r;
+    r.x = (uint32_t)float_to_bf16_bits(a) | ((uint32_t)float_to_bf16_bits(b) << 16);
+    r.y = (uint32_t)float_to_bf16_bits(c) | ((uint32_t)float_to_bf16_bits(d) << 16);
+    return r;
+}
+
+__device__ __forceinline__ void unpack4(u32x2 p, float (&f)[4])
+{
+    f[0] = __uint_as_float(p.x << 16);
+    f[1] = __uint_as_float(p.x & 0xffff0000u);
+    f[2] = __uint_as_float(p.y << 16);
+    f[3] = __uint_as_float(p.y & 0xffff0000u);
+}
+
+// Gate/up projections of one column block of d_ff: planes A = silu(G) * U, G, U.
 struct EpiGU {
-    uint16_t *G, *U, *Act;  // [tokens, d_ff]; G and U may both be NULL
+    static constexpr int NOUT = 3;
+    static constexpr bool HAS_IN = false;
+    typedef NoIn In;
+    uint16_t *G, *U, *Act;  // [tokens, d_ff]; G and U may both be NULL, Act may be NULL
     int T, dff, n_off;
-    __device__ __forceinline__ void operator()(int s, int m, int n, const float (&v)[2]) const
+    __device__ __forceinline__ In load(int, int, int) const { return In(); }
+    __device__ __forceinline__ bool enabled(int o) const { return o == 0 ? Act != nullptr : G != nullptr; }
+    __device__ __forceinline__ u32x2 pack(int o, const In &, const float (&v)[2][4]) const
     {
-        const size_t idx = ((size_t)s * T + m) * dff + n_off + n;
-        const float g = v[0], u = v[1];
-        if (G) {
-            G[idx] = float_to_bf16_bits(g);
-            U[idx] = float_to_bf16_bits(u);
-        }
-        if (Act) Act[idx] = float_to_bf16_bits(g / (1.0f + __expf(-g)) * u);
+        if (o == 1) return pack4(v[0][0], v[0][1], v[0][2], v[0][3]);
+        if (o == 2) return pack4(v[1][0], v[1][1], v[1][2], v[1][3]);
+        float a[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) a[e] = v[0][e] / (1.0f + __expf(-v[0][e])) * v[1][e];
+        return pack4(a[0], a[1], a[2], a[3]);
+    }
+    __device__ __forceinline__ uint16_t *ptr(int o, int s, int m, int n) const
+    {
+        uint16_t *base = (o == 0) ? Act : (o == 1) ? G : U;
+        return base + ((size_t)s * T + m) * dff + n_off + n;
     }
 };
 
 // C[batch][m][n] = bf16(v)
 struct EpiStore {
+    static constexpr int NOUT = 1;
+    static constexpr bool HAS_IN = false;
+    typedef NoIn In;
     uint16_t *C;
     long c_batch;
     int ldc;
-    __device__ __forceinline__ void operator()(int b, int m, int n, const float (&v)[1]) const
+    __device__ __forceinline__ In load(int, int, int) const { return In(); }
+    __device__ __forceinline__ bool enabled(int) const { return true; }
+    __device__ __forceinline__ u32x2 pack(int, const In &, const float (&v)[1][4]) const
     {
-        C[(size_t)b * c_batch + (size_t)m * ldc + n] = float_to_bf16_bits(v[0]);
+        return pack4(v[0][0], v[0][1], v[0][2], v[0][3]);
+    }
+    __device__ __forceinline__ uint16_t *ptr(int, int b, int m, int n) const
+    {
+        return C + (size_t)b * c_batch + (size_t)m * ldc + n;
     }
 };
 
 struct EpiStore2 {
+    static constexpr int NOUT = 2;
+    static constexpr bool HAS_IN = false;
+    typedef NoIn In;
     uint16_t *C0, *C1;
     long c_batch;
     int ldc;
-    __device__ __forceinline__ void operator()(int b, int m, int n, const float (&v)[2]) const
+    __device__ __forceinline__ In load(int, int, int) const { return In(); }
+    __device__ __forceinline__ bool enabled(int) const { return true; }
+    __device__ __forceinline__ u32x2 pack(int o, const In &, const float (&v)[2][4]) const
     {
-        const size_t idx = (size_t)b * c_batch + (size_t)m * ldc + n;
-        C0[idx] = float_to_bf16_bits(v[0]);
-        C1[idx] = float_to_bf16_bits(v[1]);
+        return o == 0 ? pack4(v[0][0], v[0][1], v[0][2], v[0][3]) : pack4(v[1][0], v[1][1], v[1][2], v[1][3]);
+    }
+    __device__ __forceinline__ uint16_t *ptr(int o, int b, int m, int n) const
+    {
+        return (o == 0 ? C0 : C1) + (size_t)b * c_batch + (size_t)m * ldc + n;
     }
 };
 
-// SwiGLU backward fused behind dA = dY Wd_bar^T:
+// SwiGLU backward fused behind dA = dY Wd_bar^T; planes A, dG, dU:
 //   dG = dA * U * sig(G) * (1 + G (1 - sig(G))),  dU = dA * G * sig(G),  A = G sig(G) U
 struct EpiDA {
+    static constexpr int NOUT = 3;
+    static constexpr bool HAS_IN = true;
+    struct In {
+        u32x2 g, u;
+    };
     const uint16_t *G, *U;       // saved forward activations [tokens, d_ff]
     uint16_t *dG, *dU, *Act;     // [tokens, d_ff]
     int T, dff, n_off;
-    __device__ __forceinline__ void operator()(int s, int m, int n, const float (&v)[1]) const
+    __device__ __forceinline__ In load(int s, int m, int n) const
     {
         const size_t idx = ((size_t)s * T + m) * dff + n_off + n;
-        const float g = bf16_bits_to_float(G[idx]), u = bf16_bits_to_float(U[idx]);
-        const float da = v[0];
-        const float sg = 1.0f / (1.0f + __expf(-g));
-        Act[idx] = float_to_bf16_bits(g * sg * u);
-        dG[idx] = float_to_bf16_bits(da * u * sg * (1.0f + g * (1.0f - sg)));
-        dU[idx] = float_to_bf16_bits(da * g * sg);
+        In in;
+        in.g = *reinterpret_cast<const u32x2 *>(G + idx);
+        in.u = *reinterpret_cast<const u32x2 *>(U + idx);
+        return in;
+    }
+    __device__ __forceinline__ bool enabled(int) const { return true; }
+    __device__ __forceinline__ u32x2 pack(int o, const In &in, const float (&v)[1][4]) const
+    {
+        float g[4], u[4], r[4];
+        unpack4(in.g, g);
+        unpack4(in.u, u);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float sg = 1.0f / (1.0f + __expf(-g[e]));
+            if (o == 0)
+                r[e] = g[e] * sg * u[e];
+            else if (o == 1)
+                r[e] = v[0][e] * u[e] * sg * (1.0f + g[e] * (1.0f - sg));
+            else
+                r[e] = v[0][e] * g[e] * sg;
+        }
+        return pack4(r[0], r[1], r[2], r[3]);
+    }
+    __device__ __forceinline__ uint16_t *ptr(int o, int s, int m, int n) const
+    {
+        uint16_t *base = (o == 0) ? Act : (o == 1) ? dG : dU;
+        return base + ((size_t)s * T + m) * dff + n_off + n;
     }
 };
 

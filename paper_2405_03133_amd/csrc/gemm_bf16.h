@@ -34,6 +34,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
 constexpr int BK = 64;
@@ -56,7 +57,9 @@ struct Smem {
     static constexpr int a_bytes = A_MC ? BK * tr_pitch(BM) : BM * 128;
     static constexpr int b_bytes = B_NC ? BK * tr_pitch(BN) : BN * 128;
     static constexpr int stage = a_bytes + NSET * b_bytes;
-    static constexpr int total = 2 * stage;
+    static constexpr int out_pitch = BN * 2 + 16;     // bytes per row of the epilogue staging tile
+    static constexpr int out_bytes = BM * out_pitch;
+    static constexpr int total = (2 * stage > out_bytes) ? 2 * stage : out_bytes;
 };
 
 // Swizzle of the 16-byte chunk index inside a 128-byte KC row.
@@ -163,8 +166,17 @@ __device__ __forceinline__ bf16x8 frag_tr(const char *lds, int col0, int kk, int
 
 // ---- the kernel ---------------------------------------------------------------
 //
-// Epi is a functor:  epi(batch, m, n, const float (&v)[NSET])  called once per
-// output element; consecutive lanes get consecutive n.
+// The MFMA is issued with the B fragment as its first operand, so a lane ends
+// up with one row m and, per accumulator quad, four consecutive columns n.
+//
+// Epi describes the epilogue (fused elementwise work and the output planes):
+//   Epi::NOUT                  number of output planes (bf16 matrices)
+//   Epi::In  / epi.load(b,m,n) optional per-quad inputs (four consecutive n)
+//   epi.enabled(o)             whether plane o is written at all
+//   epi.pack(o, in, v)         the four bf16 outputs of plane o for a quad, v[NSET][4] fp32
+//   epi.ptr(o, b, m, n)        global address of element (m, n) of plane o
+// Each plane is staged through LDS and leaves the workgroup as 16-byte stores
+// that are contiguous along n.
 template <int BM, int BN, int WAVES_M, int NSET, int NSRC, bool A_MC, bool B_NC, class Epi>
 __global__ __launch_bounds__(kThreads, 1) void gemm_kernel(const Params p, const Epi epi)
 {
@@ -281,7 +293,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_kernel(const Params p, const
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
                     for (int j = 0; j < NI; ++j)
-                        acc[s][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[s][j],
+                        acc[s][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[s][j], af[i],
                                                                                acc[s][i][j], 0, 0, 0);
         }
         if (more) LORY_STORE_TILE((t + 1) & 1);
@@ -290,20 +302,51 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_kernel(const Params p, const
 #undef LORY_LOAD_TILE
 #undef LORY_STORE_TILE
 
-    // accumulator element r of a 32x32 block: row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
+    // Accumulator element r of a 32x32 block now is row m = lane & 31 and column
+    // n = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3).  The loop above ended with a barrier, so
+    // the pipeline stages in LDS are free to hold the output tile.
+    typename Epi::In in[MI][NI][4];
+    if constexpr (Epi::HAS_IN) {
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
+            for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                const int n = n0 + wn0 + j * 32 + (lane & 31);
-                float v[NSET];
+                for (int rq = 0; rq < 4; ++rq) {
+                    const int m = m0 + wm0 + i * 32 + (lane & 31);
+                    const int n = n0 + wn0 + j * 32 + 8 * rq + 4 * (lane >> 5);
+                    in[i][j][rq] = epi.load(batch, m, n);
+                }
+    }
 #pragma unroll
-                for (int s = 0; s < NSET; ++s) v[s] = acc[s][i][j][r];
-                epi(batch, m, n, v);
-            }
+    for (int o = 0; o < Epi::NOUT; ++o) {
+        if (!epi.enabled(o)) continue;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    const int ml = wm0 + i * 32 + (lane & 31);
+                    const int nl = wn0 + j * 32 + 8 * rq + 4 * (lane >> 5);
+                    float v[NSET][4];
+#pragma unroll
+                    for (int s = 0; s < NSET; ++s)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[s][e] = acc[s][i][j][rq * 4 + e];
+                    const u32x2 pk = epi.pack(o, in[i][j][rq], v);
+                    *reinterpret_cast<u32x2 *>(smem + ml * SM::out_pitch + nl * 2) = pk;
+                }
+        __syncthreads();
+        constexpr int cpr = BN / 8;
+#pragma unroll 4
+        for (int idx = tid; idx < BM * cpr; idx += kThreads) {
+            const int row = idx / cpr, c = idx % cpr;
+            const u32x4 val = *reinterpret_cast<const u32x4 *>(smem + row * SM::out_pitch + c * 16);
+            *reinterpret_cast<u32x4 *>(epi.ptr(o, batch, m0 + row, n0 + c * 8)) = val;
+        }
+        __syncthreads();
+    }
 }
 
 template <int BM, int BN, int WAVES_M, int NSET, int NSRC, bool A_MC, bool B_NC, class Epi>

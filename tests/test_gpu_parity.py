@@ -160,13 +160,18 @@ BF16_CASES = [
     (LoryConfig("bf16_E33", B=1, L=256, T=64, d=64, d_ff=128, E=33, dtype="bf16", seed=34), 128 << 20),
     (LoryConfig("bf16_S40", B=5, L=512, T=64, d=64, d_ff=64, E=3, dtype="bf16", seed=35), 128 << 20),
     (LoryConfig("bf16_one_expert", B=1, L=128, T=64, d=64, d_ff=128, E=1, dtype="bf16", seed=36), 128 << 20),
+    # segment counts and lengths of the benchmark configurations at reduced widths
+    (LoryConfig("bf16_S128_E32", B=8, L=4096, T=256, d=128, d_ff=256, E=32, dtype="bf16", seed=37), 4 << 20),
+    (LoryConfig("bf16_S256_T64_E16", B=4, L=4096, T=64, d=128, d_ff=256, E=16, dtype="bf16", seed=38), 128 << 20),
+    (LoryConfig("bf16_T1024_E16", B=1, L=2048, T=1024, d=128, d_ff=256, E=16, dtype="bf16", seed=39), 128 << 20),
+    (LoryConfig("bf16_S300_E64", B=5, L=3840, T=64, d=64, d_ff=128, E=64, dtype="bf16", seed=40), 128 << 20),
 ]
 
 
 @pytest.fixture
 def default_budget():
     yield
-    lb.lory_set_slab_budget(128 << 20)
+    lb.lory_set_slab_budget(4096 << 20)
 
 
 @pytest.mark.parametrize("cfg,budget", BF16_CASES, ids=lambda v: v.name if isinstance(v, LoryConfig) else str(v))
