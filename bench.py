@@ -47,7 +47,7 @@ def cpu_baseline(cfg, verbose=False):
     from oracle import lory_oracle as orc
     from paper_2405_03133_amd.inputs import make_inputs
 
-    n_seg = 2
+    n_seg = 8
     sample = cfg.with_(B=1, L=n_seg * cfg.T)
     t = make_inputs(sample)
     t64 = {k: v.astype(np.float64) for k, v in t.items()}

@@ -11,6 +11,7 @@ hipError_t launch_dwgu(hipStream_t st, const gemm::Params &p, const EpiStore2 &e
     // The contraction is only T long, so the kernel is bound by writing its output; two
     // single-set launches with square tiles and several workgroups per CU do better than one
     // launch that shares X between the two operand sets.
+    if (gemm2::fits<2, 1>(p)) return gemm2::launch<2, 1, true, true>(p, e, st);
     if (p.N % 128 == 0 || p.N % 64 != 0) {
         gemm::Params q = p;
         EpiStore e0 = {e.C0, e.c_batch, e.ldc};
@@ -27,6 +28,7 @@ hipError_t launch_dwgu(hipStream_t st, const gemm::Params &p, const EpiStore2 &e
 hipError_t launch_dwd(hipStream_t st, const gemm::Params &p, const EpiStore &e)
 {
     // A = Act_s stored [T][d_ff] (M contiguous), B = dY_s stored [T][d] (N contiguous)
+    if (gemm2::fits<1, 1>(p)) return gemm2::launch<1, 1, true, true>(p, e, st);
     if (p.N % 128 == 0) {
         if (p.M % 128 == 0) return gemm::launch<128, 128, 2, 1, 1, true, true>(p, e, st);
         return gemm::launch<64, 128, 2, 1, 1, true, true>(p, e, st);

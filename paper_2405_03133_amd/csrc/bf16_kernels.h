@@ -3,6 +3,7 @@
 #pragma once
 
 #include "gemm_bf16.h"
+#include "gemm2_bf16.h"
 #include "merge_scatter_bf16.h"
 
 namespace lory {
@@ -40,7 +41,7 @@ struct EpiGU {
     int T, dff, n_off;
     __device__ __forceinline__ In load(int, int, int) const { return In(); }
     __device__ __forceinline__ bool enabled(int o) const { return o == 0 ? Act != nullptr : G != nullptr; }
-    __device__ __forceinline__ u32x2 pack(int o, const In &, const float (&v)[2][4]) const
+    __device__ __forceinline__ u32x2 pack(int o, int, int, int, const In &, const float (&v)[2][4]) const
     {
         if (o == 1) return pack4(v[0][0], v[0][1], v[0][2], v[0][3]);
         if (o == 2) return pack4(v[1][0], v[1][1], v[1][2], v[1][3]);
@@ -66,7 +67,7 @@ struct EpiStore {
     int ldc;
     __device__ __forceinline__ In load(int, int, int) const { return In(); }
     __device__ __forceinline__ bool enabled(int) const { return true; }
-    __device__ __forceinline__ u32x2 pack(int, const In &, const float (&v)[1][4]) const
+    __device__ __forceinline__ u32x2 pack(int, int, int, int, const In &, const float (&v)[1][4]) const
     {
         return pack4(v[0][0], v[0][1], v[0][2], v[0][3]);
     }
@@ -85,57 +86,13 @@ struct EpiStore2 {
     int ldc;
     __device__ __forceinline__ In load(int, int, int) const { return In(); }
     __device__ __forceinline__ bool enabled(int) const { return true; }
-    __device__ __forceinline__ u32x2 pack(int o, const In &, const float (&v)[2][4]) const
+    __device__ __forceinline__ u32x2 pack(int o, int, int, int, const In &, const float (&v)[2][4]) const
     {
         return o == 0 ? pack4(v[0][0], v[0][1], v[0][2], v[0][3]) : pack4(v[1][0], v[1][1], v[1][2], v[1][3]);
     }
     __device__ __forceinline__ uint16_t *ptr(int o, int b, int m, int n) const
     {
         return (o == 0 ? C0 : C1) + (size_t)b * c_batch + (size_t)m * ldc + n;
-    }
-};
-
-// SwiGLU backward fused behind dA = dY Wd_bar^T; planes A, dG, dU:
-//   dG = dA * U * sig(G) * (1 + G (1 - sig(G))),  dU = dA * G * sig(G),  A = G sig(G) U
-struct EpiDA {
-    static constexpr int NOUT = 3;
-    static constexpr bool HAS_IN = true;
-    struct In {
-        u32x2 g, u;
-    };
-    const uint16_t *G, *U;       // saved forward activations [tokens, d_ff]
-    uint16_t *dG, *dU, *Act;     // [tokens, d_ff]
-    int T, dff, n_off;
-    __device__ __forceinline__ In load(int s, int m, int n) const
-    {
-        const size_t idx = ((size_t)s * T + m) * dff + n_off + n;
-        In in;
-        in.g = *reinterpret_cast<const u32x2 *>(G + idx);
-        in.u = *reinterpret_cast<const u32x2 *>(U + idx);
-        return in;
-    }
-    __device__ __forceinline__ bool enabled(int) const { return true; }
-    __device__ __forceinline__ u32x2 pack(int o, const In &in, const float (&v)[1][4]) const
-    {
-        float g[4], u[4], r[4];
-        unpack4(in.g, g);
-        unpack4(in.u, u);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float sg = 1.0f / (1.0f + __expf(-g[e]));
-            if (o == 0)
-                r[e] = g[e] * sg * u[e];
-            else if (o == 1)
-                r[e] = v[0][e] * u[e] * sg * (1.0f + g[e] * (1.0f - sg));
-            else
-                r[e] = v[0][e] * g[e] * sg;
-        }
-        return pack4(r[0], r[1], r[2], r[3]);
-    }
-    __device__ __forceinline__ uint16_t *ptr(int o, int s, int m, int n) const
-    {
-        uint16_t *base = (o == 0) ? Act : (o == 1) ? dG : dU;
-        return base + ((size_t)s * T + m) * dff + n_off + n;
     }
 };
 
@@ -150,7 +107,9 @@ void scatter_partial_dims(int S, int E, int *rows, int *cols);
 
 hipError_t launch_gu(hipStream_t st, const gemm::Params &p, const EpiGU &e);     // X * [Wg_bar | Wu_bar]
 hipError_t launch_down(hipStream_t st, const gemm::Params &p, const EpiStore &e);  // A * Wd_bar
-hipError_t launch_da(hipStream_t st, const gemm::Params &p, const EpiDA &e);     // dY * Wd_bar^T
+hipError_t launch_da(hipStream_t st, const gemm::Params &p, const EpiStore &e);  // dY * Wd_bar^T
+hipError_t launch_swiglu_bwd(hipStream_t st, const uint16_t *G, const uint16_t *U, uint16_t *dG_dA,
+                             uint16_t *dU, uint16_t *Act, long rows, int dff, int n0, int nf);
 hipError_t launch_dx(hipStream_t st, const gemm::Params &p, const EpiStore &e);  // dG Wg_bar^T + dU Wu_bar^T
 hipError_t launch_dwgu(hipStream_t st, const gemm::Params &p, const EpiStore2 &e);  // X^T [dG | dU]
 hipError_t launch_dwd(hipStream_t st, const gemm::Params &p, const EpiStore &e);  // A^T dY

@@ -21,7 +21,6 @@ namespace lory {
 namespace {
 
 using gemm::Params;
-using k::EpiDA;
 using k::EpiGU;
 using k::EpiStore;
 using k::EpiStore2;
@@ -256,17 +255,21 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
             const Rect rows_d = rect(m.D, m.d, n0, nf, 0, m.d);      // rows n0.. of Wd [d_ff, d]
             const Rect cols_f = rect(m.D, m.dff, 0, m.d, n0, nf);    // columns n0.. of Wg/Wu [d, d_ff]
 
-            // dA = dY Wd_bar^T for these d_ff columns, then dG, dU, A
+            // dA = dY Wd_bar^T for these d_ff columns, then the SwiGLU backward pass: dG, dU, A
             LORY_TRY(merge(st, wc, S, m.E, Wd, rows_d, s_md));
             {
                 Params p = {};
                 p.A[0] = dYc; p.a_batch[0] = TD; p.lda[0] = m.d;
                 p.B[0] = s_md; p.b_batch[0] = (long)nf * m.d; p.ldb[0] = m.d;
                 p.M = m.T; p.N = nf; p.K = m.d; p.batches = S;
-                EpiDA epi = {Gc, Uc, dG, dU, Act, m.T, m.dff, n0};
-                prof::Range r(st, prof::kGemmDA, gemm_flops(p, 1, 1),
-                              2.0 * ((double)S * TD + (double)S * nf * m.d + 5.0 * S * m.T * nf));
-                LORY_TRY(k::launch_da(st, p, epi));
+                EpiStore epi = {dG + n0, TF, m.dff};  // dA parks in the dG buffer
+                {
+                    prof::Range r(st, prof::kGemmDA, gemm_flops(p, 1, 1),
+                                  2.0 * ((double)S * TD + (double)S * nf * m.d + (double)S * m.T * nf));
+                    LORY_TRY(k::launch_da(st, p, epi));
+                }
+                prof::Range r2(st, prof::kSwigluBwd, 12.0 * S * m.T * nf, 2.0 * 6.0 * S * m.T * nf);
+                LORY_TRY(k::launch_swiglu_bwd(st, Gc, Uc, dG, dU, Act, (long)S * m.T, m.dff, n0, nf));
             }
             // dWd_bar rows = A^T dY
             {

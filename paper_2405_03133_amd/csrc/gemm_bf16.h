@@ -173,7 +173,7 @@ __device__ __forceinline__ bf16x8 frag_tr(const char *lds, int col0, int kk, int
 //   Epi::NOUT                  number of output planes (bf16 matrices)
 //   Epi::In  / epi.load(b,m,n) optional per-quad inputs (four consecutive n)
 //   epi.enabled(o)             whether plane o is written at all
-//   epi.pack(o, in, v)         the four bf16 outputs of plane o for a quad, v[NSET][4] fp32
+//   epi.pack(o, b, m, n, in, v) the four bf16 outputs of plane o for the quad at (m, n..n+3), v[NSET][4] fp32
 //   epi.ptr(o, b, m, n)        global address of element (m, n) of plane o
 // Each plane is staged through LDS and leaves the workgroup as 16-byte stores
 // that are contiguous along n.
@@ -334,7 +334,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_kernel(const Params p, const
                     for (int s = 0; s < NSET; ++s)
 #pragma unroll
                         for (int e = 0; e < 4; ++e) v[s][e] = acc[s][i][j][rq * 4 + e];
-                    const u32x2 pk = epi.pack(o, in[i][j][rq], v);
+                    const u32x2 pk = epi.pack(o, batch, m0 + ml, n0 + nl, in[i][j][rq], v);
                     *reinterpret_cast<u32x2 *>(smem + ml * SM::out_pitch + nl * 2) = pk;
                 }
         __syncthreads();

@@ -25,7 +25,7 @@ std::vector<Record> g_records;
 std::vector<hipEvent_t> g_pool;
 
 const char *const kNames[kNumClasses] = {"route",     "merge",     "gemm_gate_up", "gemm_down",
-                                         "gemm_dA",   "gemm_dX",   "gemm_dW_gate_up",
+                                         "gemm_dA",   "swiglu_bwd", "gemm_dX",   "gemm_dW_gate_up",
                                          "gemm_dW_down", "scatter_dots", "dw_reduce"};
 
 hipEvent_t get_event()
