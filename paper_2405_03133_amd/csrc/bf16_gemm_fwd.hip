@@ -5,14 +5,26 @@
 namespace lory {
 namespace k {
 
-hipError_t launch_gu(hipStream_t st, const gemm::Params &p, const EpiGU &e)
+namespace {
+template <bool SAVE, bool ACT>
+hipError_t launch_gu_t(hipStream_t st, const gemm::Params &p, const EpiGU &d)
 {
     // A = X_s [T][d] (K contiguous), B = merged slabs [d][nf] (N contiguous), two sets
+    const EpiGUT<SAVE, ACT> e = {d.G, d.U, d.Act, d.T, d.dff, d.n_off};
     if (gemm2::fits<2, 1>(p)) return gemm2::launch<2, 1, false, true>(p, e, st);
     if (p.M % 256 == 0 && p.N % 128 == 0) return gemm::launch<256, 128, 2, 2, 1, false, true>(p, e, st);
     if (p.M % 256 == 0) return gemm::launch<256, 64, 2, 2, 1, false, true>(p, e, st);
     if (p.M % 128 == 0) return gemm::launch<128, 64, 2, 2, 1, false, true>(p, e, st);
     return gemm::launch<64, 64, 2, 2, 1, false, true>(p, e, st);
+}
+}  // namespace
+
+hipError_t launch_gu(hipStream_t st, const gemm::Params &p, const EpiGU &e)
+{
+    const bool save = e.G != nullptr, act = e.Act != nullptr;
+    if (save && act) return launch_gu_t<true, true>(st, p, e);
+    if (act) return launch_gu_t<false, true>(st, p, e);
+    return launch_gu_t<true, false>(st, p, e);
 }
 
 hipError_t launch_down(hipStream_t st, const gemm::Params &p, const EpiStore &e)

@@ -19,8 +19,8 @@ struct NoIn {};
 __device__ __forceinline__ u32x2 pack4(float a, float b, float c, float d)
 {
     u32x2 r;
-    r.x = (uint32_t)float_to_bf16_bits(a) | ((uint32_t)float_to_bf16_bits(b) << 16);
-    r.y = (uint32_t)float_to_bf16_bits(c) | ((uint32_t)float_to_bf16_bits(d) << 16);
+    r.x = gemm::cvt_pk_bf16(a, b);
+    r.y = gemm::cvt_pk_bf16(c, d);
     return r;
 }
 
@@ -33,21 +33,24 @@ __device__ __forceinline__ void unpack4(u32x2 p, float (&f)[4])
 }
 
 // Gate/up projections of one column block of d_ff: planes A = silu(G) * U, G, U.
-struct EpiGU {
+// SAVE: write G and U; ACT: write A.  (Compile-time so that the epilogue has no data-dependent
+// control flow.)
+template <bool SAVE, bool ACT>
+struct EpiGUT {
     static constexpr int NOUT = 3;
     static constexpr bool HAS_IN = false;
     typedef NoIn In;
-    uint16_t *G, *U, *Act;  // [tokens, d_ff]; G and U may both be NULL, Act may be NULL
+    uint16_t *G, *U, *Act;  // [tokens, d_ff]
     int T, dff, n_off;
     __device__ __forceinline__ In load(int, int, int) const { return In(); }
-    __device__ __forceinline__ bool enabled(int o) const { return o == 0 ? Act != nullptr : G != nullptr; }
+    __device__ __forceinline__ bool enabled(int o) const { return o == 0 ? ACT : SAVE; }
     __device__ __forceinline__ u32x2 pack(int o, int, int, int, const In &, const float (&v)[2][4]) const
     {
         if (o == 1) return pack4(v[0][0], v[0][1], v[0][2], v[0][3]);
         if (o == 2) return pack4(v[1][0], v[1][1], v[1][2], v[1][3]);
         float a[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) a[e] = v[0][e] / (1.0f + __expf(-v[0][e])) * v[1][e];
+        for (int e = 0; e < 4; ++e) a[e] = v[0][e] * __builtin_amdgcn_rcpf(1.0f + __expf(-v[0][e])) * v[1][e];
         return pack4(a[0], a[1], a[2], a[3]);
     }
     __device__ __forceinline__ uint16_t *ptr(int o, int s, int m, int n) const
@@ -55,6 +58,12 @@ struct EpiGU {
         uint16_t *base = (o == 0) ? Act : (o == 1) ? G : U;
         return base + ((size_t)s * T + m) * dff + n_off + n;
     }
+};
+
+// Run-time description of the same epilogue (G and U may both be NULL, Act may be NULL).
+struct EpiGU {
+    uint16_t *G, *U, *Act;
+    int T, dff, n_off;
 };
 
 // C[batch][m][n] = bf16(v)
@@ -108,6 +117,8 @@ void scatter_partial_dims(int S, int E, int *rows, int *cols);
 hipError_t launch_gu(hipStream_t st, const gemm::Params &p, const EpiGU &e);     // X * [Wg_bar | Wu_bar]
 hipError_t launch_down(hipStream_t st, const gemm::Params &p, const EpiStore &e);  // A * Wd_bar
 hipError_t launch_da(hipStream_t st, const gemm::Params &p, const EpiStore &e);  // dY * Wd_bar^T
+hipError_t launch_swiglu_fwd(hipStream_t st, const uint16_t *G, const uint16_t *U, uint16_t *Act, long rows,
+                             int dff, int n0, int nf);
 hipError_t launch_swiglu_bwd(hipStream_t st, const uint16_t *G, const uint16_t *U, uint16_t *dG_dA,
                              uint16_t *dU, uint16_t *Act, long rows, int dff, int n0, int nf);
 hipError_t launch_dx(hipStream_t st, const gemm::Params &p, const EpiStore &e);  // dG Wg_bar^T + dU Wu_bar^T

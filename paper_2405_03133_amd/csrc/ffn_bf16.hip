@@ -143,11 +143,22 @@ hipError_t gate_up_block(hipStream_t st, const Dims &m, int S, const bf *X, cons
     p.B[0] = sg; p.b_batch[0] = (long)m.d * nf; p.ldb[0] = nf;
     p.B[1] = su; p.b_batch[1] = (long)m.d * nf; p.ldb[1] = nf;
     p.M = m.T; p.N = nf; p.K = m.d; p.batches = S;
-    EpiGU epi = {G, U, Act, m.T, m.dff, n0};
-    const double out_elems = (double)S * m.T * nf * ((G ? 2 : 0) + (Act ? 1 : 0));
-    prof::Range r(st, prof::kGemmGU, gemm_flops(p, 2, 1),
-                  2.0 * ((double)S * m.T * m.d + 2.0 * S * m.d * nf + out_elems));
-    return k::launch_gu(st, p, epi);
+    // With G and U saved anyway, the activation A = silu(G) * U is cheaper as a streaming pass
+    // over them than as a third output plane of the GEMM epilogue; without saved G, U it is
+    // computed in the epilogue from the fp32 accumulators.
+    const bool split = (G != nullptr && Act != nullptr);
+    EpiGU epi = {G, U, split ? nullptr : Act, m.T, m.dff, n0};
+    const double out_elems = (double)S * m.T * nf * ((G ? 2 : 0) + ((Act && !split) ? 1 : 0));
+    {
+        prof::Range r(st, prof::kGemmGU, gemm_flops(p, 2, 1),
+                      2.0 * ((double)S * m.T * m.d + 2.0 * S * m.d * nf + out_elems));
+        if ((e = k::launch_gu(st, p, epi)) != hipSuccess) return e;
+    }
+    if (split) {
+        prof::Range r(st, prof::kSwigluFwd, 4.0 * S * m.T * nf, 2.0 * 3.0 * S * m.T * nf);
+        return k::launch_swiglu_fwd(st, G, U, Act, (long)S * m.T, m.dff, n0, nf);
+    }
+    return hipSuccess;
 }
 
 }  // namespace

@@ -41,9 +41,9 @@ struct Smem {
     static constexpr int BN = 256;  // columns of the tile over all operand sets
     static constexpr int BNS = BN / NSET;
     static constexpr int ring = kStages * kStageBytes;
-    static constexpr int out_pitch = BNS * 2 + 16;
-    static constexpr int out_bytes = BM * out_pitch;
-    static constexpr int total = ring > out_bytes ? ring : out_bytes;
+    // epilogue staging: every wave owns 32 rows x (BNS / 2) columns of bf16, no padding
+    static constexpr int stage_out = 32 * (BNS / 2) * 2;
+    static constexpr int total = ring + 4 * stage_out;
 };
 
 __device__ __forceinline__ int fkc(int row)
@@ -126,6 +126,10 @@ __device__ __forceinline__ void ring_barrier()
     asm volatile("" ::: "memory");
 }
 
+// Persistent kernel: the grid is one workgroup per CU (a multiple of 8); every workgroup walks
+// its own list of tiles, and the K steps of consecutive tiles form one stream through the
+// ring, so the first operands of the next tile are already in flight while the current tile
+// is multiplied and written out.
 template <int NSET, int NSRC, bool A_MC, bool B_NC, class Epi>
 __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, const Epi epi)
 {
@@ -135,6 +139,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
     constexpr int WN = BNS / 2;           // columns per wave and set
     constexpr int MI = 4, NI = WN / 32;   // 128 x WN per wave and set
     constexpr int BSET_BYTES = kOperandBytes / NSET;
+    static_assert(NSET * NI == 4, "a wave multiplies 4 A blocks with 4 B blocks per K slice");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -146,71 +151,96 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
 
-    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD a
-    // contiguous range of tiles so that the tiles of one segment, which share the A operand,
-    // meet in the same L2.
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Every XCD gets a
+    // contiguous range of tiles, shared cyclically by its workgroups, so that the tiles of one
+    // segment, which share the A operand, meet in the same L2.
     const int tiles_n = p.N / BNS;
     const int tiles_m = p.M / BM;
     const int ntiles = p.batches * tiles_m * tiles_n;
     const int per_xcd = (ntiles + 7) >> 3;
-    int bid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (bid >= ntiles) return;
-    const int nt = bid % tiles_n;
-    bid /= tiles_n;
-    const int mt = bid % tiles_m;
-    const int batch = bid / tiles_m;
-    const int m0 = mt * BM, n0 = nt * BNS;
+    const int wg_per_xcd = gridDim.x >> 3;
+    const int xcd = blockIdx.x & 7, qx = blockIdx.x >> 3;
+    int xcd_tiles = ntiles - xcd * per_xcd;  // tiles in this XCD's range
+    if (xcd_tiles > per_xcd) xcd_tiles = per_xcd;
+    const int my_tiles = (xcd_tiles > qx) ? (xcd_tiles - qx + wg_per_xcd - 1) / wg_per_xcd : 0;
+    if (my_tiles == 0) return;
 
     const int ktiles = p.K / BK;
-    const int total = ktiles * NSRC;
+    const int total = ktiles * NSRC;   // K steps per tile
+    const int G = my_tiles * total;    // K steps of this workgroup
 
-    // per-lane element offsets of this wave's 4 + 4 chunks per stage
+    // per-lane element offsets of this wave's 4 + 4 chunks per stage, relative to the tile origin
     long offA[4], offB[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int L = (wave * 4 + i) * 64 + lane;  // LDS chunk position inside a 16 KB operand tile
-        offA[i] = A_MC ? chunk_off_tr<BM>(L, p.lda[0], m0) : chunk_off_kc(L, p.lda[0], m0);
-        const int set = (NSET == 2) ? (L >> 9) : 0;
+        offA[i] = A_MC ? chunk_off_tr<BM>(L, p.lda[0], 0) : chunk_off_kc(L, p.lda[0], 0);
         const int Ls = (NSET == 2) ? (L & 511) : L;
-        (void)set;
-        offB[i] = B_NC ? chunk_off_tr<BNS>(Ls, p.ldb[0], n0) : chunk_off_kc(Ls, p.ldb[0], n0);
+        offB[i] = B_NC ? chunk_off_tr<BNS>(Ls, p.ldb[0], 0) : chunk_off_kc(Ls, p.ldb[0], 0);
     }
     const long kstepA = A_MC ? (long)BK * p.lda[0] : BK;
     const long kstepB = B_NC ? (long)BK * p.ldb[0] : BK;
 
-    // One of the 8 direct loads this wave contributes to K step t: i < 4 -> A chunk i, else B chunk i - 4.
-    auto issue_one = [&](int t, int i) {
+    auto tile_coords = [&](int i, int &batch, int &m0, int &n0) {
+        int id = xcd * per_xcd + qx + i * wg_per_xcd;
+        const int nt = id % tiles_n;
+        id /= tiles_n;
+        const int mt = id % tiles_m;
+        batch = id / tiles_m;
+        m0 = mt * BM;
+        n0 = nt * BNS;
+    };
+
+    // origin (in elements) of the tile the load stream is currently in
+    int ld_tile = -1;
+    long tileA = 0, tileB = 0;
+    int ld_batch = 0;
+    auto enter_tile = [&](int i) {
+        int m0, n0;
+        tile_coords(i, ld_batch, m0, n0);
+        tileA = A_MC ? (long)m0 : (long)m0 * p.lda[0];
+        tileB = B_NC ? (long)n0 : (long)n0 * p.ldb[0];
+        ld_tile = i;
+    };
+
+    // One of the 8 direct loads this wave contributes to K step g of its stream:
+    // i < 4 -> A chunk i, else B chunk i - 4.
+    // (gsrc = K step whose operands are fetched, gslot = K step whose ring slot receives them)
+    auto issue_one = [&](int gsrc, int gslot, int i) {
+        const int t = gsrc % total;
         const int src = (NSRC == 2) ? (t / ktiles) : 0;
         const int ks = t % ktiles;
-        const uint32_t stage = lds0 + (t & (kStages - 1)) * kStageBytes + wave_u * 4096;
+        const uint32_t stage = lds0 + (gslot & (kStages - 1)) * kStageBytes + wave_u * 4096;
         if (i < 4) {
-            const uint16_t *a = p.A[src] + (size_t)batch * p.a_batch[src] + ks * kstepA;
+            const uint16_t *a = p.A[src] + (size_t)ld_batch * p.a_batch[src] + tileA + ks * kstepA;
             dma16(a + offA[i], stage + i * 1024);
         } else {
             const int j = i - 4;
             const int set = (NSET == 2) ? ((wave * 4 + j) >> 3) : 0;  // 8 KB = 8 wave-loads per set
             const int bi = (NSRC == 2) ? src : set;
-            const uint16_t *b = p.B[bi] + (size_t)batch * p.b_batch[bi] + ks * kstepB;
+            const uint16_t *b = p.B[bi] + (size_t)ld_batch * p.b_batch[bi] + tileB + ks * kstepB;
             dma16(b + offB[j], stage + kOperandBytes + j * 1024);
         }
     };
 
     f32x16 acc[NSET][MI][NI];
+    auto zero_acc = [&]() {
 #pragma unroll
-    for (int s = 0; s < NSET; ++s)
+        for (int s = 0; s < NSET; ++s)
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < NI; ++j)
+                for (int j = 0; j < NI; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[s][i][j][r] = 0.f;
+                    for (int r = 0; r < 16; ++r) acc[s][i][j][r] = 0.f;
+    };
 
+    for (int g = 0; g < kStages - 1; ++g) {
+        const int gsrc = g < G ? g : G - 1;
+        if (gsrc / total != ld_tile) enter_tile(gsrc / total);
 #pragma unroll
-    for (int t = 0; t < kStages - 1; ++t)
-        if (t < total) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) issue_one(t, i);
-        }
+        for (int i = 0; i < 8; ++i) issue_one(gsrc, g, i);
+    }
 
     // Fragment f of a 16-wide K slice: f < 4 -> A rows block f, else B columns block f - 4
     // (blocks of B count through the operand sets).
@@ -229,28 +259,31 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
                 bfr[q] = frag_kc(lb, wn0 + j * 32, kk, lane);
         }
     };
-    static_assert(NSET * NI == 4, "a wave multiplies 4 A blocks with 4 B blocks per K slice");
 
     // The 16 MFMAs of a K slice are issued one per "slot"; every slot also carries one LDS
     // fragment read for the next slice or one direct load for the ring, so that those issue
     // in the shadow of the matrix pipe instead of between bursts.  Fragments are double
-    // buffered in registers.  The single barrier of an iteration sits between the two slices
-    // of K step t: by then every wave has finished reading step t-1 (its ring slot may be
-    // refilled with step t+3) and step t+1 has landed for everyone (its first slice can be
-    // fetched behind the second slice's MFMAs).
+    // buffered in registers.  The single barrier of a K step sits between its two slices: by
+    // then every wave has finished reading step g-1 (its ring slot may be refilled with step
+    // g+3) and step g+1 has landed for everyone (its first slice can be fetched behind the
+    // second slice's MFMAs).
     bf16x8 a0[MI], b0[NSET * NI], a1[MI], b1[NSET * NI];
     wait_vmcnt<(kStages - 2) * 8>();  // steps 1 and 2 may still be in flight
-    if (total < kStages - 1) wait_vmcnt<0>();
     ring_barrier();
 #pragma unroll
     for (int f = 0; f < 8; ++f) load_frag(smem, 0, f, a0, b0);
 
-    // REFILL: a K step t+3 exists and is requested now; MORE: a K step t+1 exists.
-    auto step = [&](int t, auto refill_c, auto more_c) {
-        constexpr bool REFILL = decltype(refill_c)::value;
-        constexpr bool MORE = decltype(more_c)::value;
-        const char *la = smem + (t & (kStages - 1)) * kStageBytes;
-        const char *ln = smem + ((t + 1) & (kStages - 1)) * kStageBytes;
+    // One K step.  The code is the same for every step: past the end of the stream the refill
+    // simply re-fetches the last K step into the ring slot that has just become free and the
+    // fragment prefetch reads a slot nobody will use, so there is exactly one group of 8 loads
+    // in flight per step and "all but the newest group have landed" (vmcnt(8)) always means
+    // "step g+1 is complete".
+    // EXTRA: store instructions of the previous tile's epilogue that were issued after the loads
+    // of step g+1 and may therefore still be pending (loads and stores share vmcnt and retire
+    // in order); only non-zero for the first two steps of a tile.
+    auto step = [&](int g, int extra_now) {
+        const char *la = smem + (g & (kStages - 1)) * kStageBytes;
+        const char *ln = smem + ((g + 1) & (kStages - 1)) * kStageBytes;
 #pragma unroll
         for (int sl = 0; sl < 16; ++sl) {
             const int i = sl >> 2, q = sl & 3;
@@ -258,74 +291,87 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
             if ((sl & 1) == 0) load_frag(la, 1, sl >> 1, a1, b1);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // step t+1 complete for this wave: at most step t+2 pending
-        if constexpr (REFILL)
-            wait_vmcnt<8>();  // REFILL implies that step t+2 exists
+        if (extra_now == 32)
+            wait_vmcnt<40>();
+        else if (extra_now == 16)
+            wait_vmcnt<24>();
         else
-            wait_vmcnt<0>();
+            wait_vmcnt<8>();
         ring_barrier();
+        const int gsrc = (g + kStages - 1 < G) ? (g + kStages - 1) : (G - 1);  // K step to fetch
+        if (gsrc / total != ld_tile) enter_tile(gsrc / total);
 #pragma unroll
         for (int sl = 0; sl < 16; ++sl) {
             const int i = sl >> 2, q = sl & 3;
             acc[q / NI][i][q % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1[q], a1[i], acc[q / NI][i][q % NI], 0, 0, 0);
-            if ((sl & 1) == 0) {
-                if constexpr (MORE) load_frag(ln, 0, sl >> 1, a0, b0);
-            } else {
-                if constexpr (REFILL) issue_one(t + kStages - 1, sl >> 1);
-            }
+            if ((sl & 1) == 0)
+                load_frag(ln, 0, sl >> 1, a0, b0);
+            else
+                issue_one(gsrc, g + kStages - 1, sl >> 1);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    using std::false_type;
-    using std::true_type;
-    int t = 0;
-    for (; t + kStages - 1 < total; ++t) step(t, true_type(), true_type());
-    for (; t + 1 < total; ++t) step(t, false_type(), true_type());
-    if (t < total) step(t, false_type(), false_type());
-    __syncthreads();  // the ring is idle: reuse it as the output staging tile
 
-    typename Epi::In in[MI][NI][4];
-    if constexpr (Epi::HAS_IN) {
+    // Epilogue of one tile, wave-local: the wave's 128 x WN sub-tile leaves in blocks of 32 rows
+    // through the wave's own staging area (XOR-swizzled 16-byte chunks), as 16-byte stores that
+    // are contiguous along n.  Accumulator element r of a 32x32 block is row m = lane & 31,
+    // column n = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3).
+    char *stg = smem + SM::ring + wave * SM::stage_out;
+    constexpr int CP = WN / 8;  // 16-byte chunks per staged row
+    auto epilogue = [&](int tile_i) {
+        int batch, m0, n0;
+        tile_coords(tile_i, batch, m0, n0);
+        const int r = lane & 31, h = lane >> 5;
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i) {
+            // all planes of one 32-row block before the next block: its accumulators are read
+            // into registers once
 #pragma unroll
-            for (int j = 0; j < NI; ++j)
+            for (int o = 0; o < Epi::NOUT; ++o) {
+                if (!epi.enabled(o)) continue;
 #pragma unroll
-                for (int rq = 0; rq < 4; ++rq) {
-                    const int m = m0 + wm0 + i * 32 + (lane & 31);
-                    const int n = n0 + wn0 + j * 32 + 8 * rq + 4 * (lane >> 5);
-                    in[i][j][rq] = epi.load(batch, m, n);
+                for (int j = 0; j < NI; ++j)
+#pragma unroll
+                    for (int rq = 0; rq < 4; ++rq) {
+                        const int nl = j * 32 + 8 * rq + 4 * h;  // column inside the wave's WN columns
+                        float v[NSET][4];
+#pragma unroll
+                        for (int s = 0; s < NSET; ++s)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[s][e] = acc[s][i][j][rq * 4 + e];
+                        const u32x2 pk = epi.pack(o, batch, m0 + wm0 + i * 32 + r, n0 + wn0 + nl, typename Epi::In(), v);
+                        const int c = nl >> 3;
+                        *reinterpret_cast<u32x2 *>(stg + r * (WN * 2) + ((c ^ (r & (CP - 1))) << 4) + h * 8) = pk;
+                        __builtin_amdgcn_sched_barrier(0);  // one quad at a time: keeps register use flat
+                    }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int it = 0; it < (32 * CP) / 64; ++it) {
+                    const int idx = it * 64 + lane;
+                    const int row = idx / CP, c = idx % CP;
+                    const u32x4 val = *reinterpret_cast<const u32x4 *>(stg + row * (WN * 2) + ((c ^ (row & (CP - 1))) << 4));
+                    *reinterpret_cast<u32x4 *>(epi.ptr(o, batch, m0 + wm0 + i * 32 + row, n0 + wn0 + c * 8)) = val;
                 }
-    }
-#pragma unroll
-    for (int o = 0; o < Epi::NOUT; ++o) {
-        if (!epi.enabled(o)) continue;
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int rq = 0; rq < 4; ++rq) {
-                    const int ml = wm0 + i * 32 + (lane & 31);
-                    const int nl = wn0 + j * 32 + 8 * rq + 4 * (lane >> 5);
-                    float v[NSET][4];
-#pragma unroll
-                    for (int s = 0; s < NSET; ++s)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[s][e] = acc[s][i][j][rq * 4 + e];
-                    const u32x2 pk = epi.pack(o, batch, m0 + ml, n0 + nl, in[i][j][rq], v);
-                    *reinterpret_cast<u32x2 *>(smem + ml * SM::out_pitch + nl * 2) = pk;
-                }
-        __syncthreads();
-        constexpr int cpr = BNS / 8;
-#pragma unroll 4
-        for (int idx = tid; idx < BM * cpr; idx += kThreads) {
-            const int row = idx / cpr, c = idx % cpr;
-            const u32x4 val = *reinterpret_cast<const u32x4 *>(smem + row * SM::out_pitch + c * 16);
-            *reinterpret_cast<u32x4 *>(epi.ptr(o, batch, m0 + row, n0 + c * 8)) = val;
+                __builtin_amdgcn_wave_barrier();
+            }
         }
-        __syncthreads();
+    };
+
+    // 16-byte store instructions a wave issues per tile epilogue
+    int nst = 0;
+#pragma unroll
+    for (int o = 0; o < Epi::NOUT; ++o)
+        if (epi.enabled(o)) nst += MI * ((32 * CP) / 64);
+    const int extra = (total >= 2) ? (nst >= 32 ? 32 : (nst >= 16 ? 16 : 0)) : 0;
+    int g = 0;
+    for (int tile_i = 0; tile_i < my_tiles; ++tile_i) {
+        zero_acc();
+        // the first two K steps of a tile run while the previous tile's stores drain
+        const int relaxed = (tile_i > 0) ? 2 : 0;
+        for (int t = 0; t < total; ++t, ++g) step(g, t < relaxed ? extra : 0);
+        epilogue(tile_i);
     }
+    wait_vmcnt<0>();  // no direct load may still be writing LDS when the workgroup retires
 }
 
 // Shapes this kernel accepts.
@@ -336,6 +382,19 @@ inline bool fits(const Params &p)
     if (NSRC == 2 && (p.lda[0] != p.lda[1] || p.ldb[0] != p.ldb[1])) return false;
     if (NSET == 2 && p.ldb[0] != p.ldb[1]) return false;
     return true;
+}
+
+inline int persistent_grid()
+{
+    static int grid = 0;
+    if (grid == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
+            cus = 256;
+        grid = cus / 8 * 8;
+    }
+    return grid;
 }
 
 template <int NSET, int NSRC, bool A_MC, bool B_NC, class Epi>
@@ -351,7 +410,8 @@ inline hipError_t launch(const Params &p, const Epi &epi, hipStream_t st)
         configured = true;
     }
     const long ntiles = (long)p.batches * (p.M / BM) * (p.N / SM::BNS);
-    const long blocks = (ntiles + 7) / 8 * 8;  // the kernel re-maps block ids per XCD and drops the excess
+    long blocks = (ntiles + 7) / 8 * 8;
+    if (blocks > persistent_grid()) blocks = persistent_grid();  // one workgroup per CU walks several tiles
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kThreads), SM::total, st, p, epi);
     return hipGetLastError();
 }

@@ -78,6 +78,21 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
     return (uint16_t)(u >> 16);
 }
 
+// Two floats -> two bf16 (round to nearest even) packed into 32 bits, low half first: a single
+// v_cvt_pk_bf16_f32 on gfx950.
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    union {
+        bf16x2 b;
+        uint32_t u;
+    } r;
+    r.b = __builtin_convertvector(v, bf16x2);
+    return r.u;
+}
+
 // ---- global -> register -> LDS staging of one K step --------------------------
 //
 // KC tile (ROWS rows of 64 bf16): thread t moves chunk (t & 7) of rows (t >> 3) + 32 i.

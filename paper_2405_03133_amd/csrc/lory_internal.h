@@ -42,7 +42,7 @@ inline int launch_status()
 
 // ---- optional event timing per kernel class (profile.hip)
 namespace prof {
-enum Class { kRoute = 0, kMerge, kGemmGU, kGemmDown, kGemmDA, kSwigluBwd, kGemmDX, kGemmDWGU, kGemmDWD, kScatter,
+enum Class { kRoute = 0, kMerge, kGemmGU, kSwigluFwd, kGemmDown, kGemmDA, kSwigluBwd, kGemmDX, kGemmDWGU, kGemmDWD, kScatter,
              kDwReduce, kNumClasses };
 bool enabled();
 int set_enabled(int on);

@@ -68,7 +68,7 @@ __device__ __forceinline__ void transpose8x8(const Frag (&in)[8], Frag (&out)[8]
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 {
-    return (uint32_t)gemm::float_to_bf16_bits(lo) | ((uint32_t)gemm::float_to_bf16_bits(hi) << 16);
+    return gemm::cvt_pk_bf16(lo, hi);
 }
 
 // Eight fp32 routing weights -> bf16 hi and lo operand fragments.

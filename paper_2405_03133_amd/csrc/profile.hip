@@ -24,7 +24,7 @@ bool g_on = false;
 std::vector<Record> g_records;
 std::vector<hipEvent_t> g_pool;
 
-const char *const kNames[kNumClasses] = {"route",     "merge",     "gemm_gate_up", "gemm_down",
+const char *const kNames[kNumClasses] = {"route",     "merge",     "gemm_gate_up", "swiglu_fwd", "gemm_down",
                                          "gemm_dA",   "swiglu_bwd", "gemm_dX",   "gemm_dW_gate_up",
                                          "gemm_dW_down", "scatter_dots", "dw_reduce"};
 
