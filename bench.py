@@ -22,9 +22,15 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE);
-# filled in from profiles/ once measured, else None.
-TRAFFIC_BYTES = {}
+# HBM bytes per launch (average over the launches of a step) from the rocprofv3 --pmc runs summarised in
+# profiles/hbm_traffic_C4_fwd_bwd.txt: FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the factors that make a plain
+# 1 GiB device copy read 1 GiB and write 1 GiB.  Only valid for the default launch configuration.
+TRAFFIC_BYTES = {
+    ("C4", "merge"): 1.899e9,
+    ("C4", "scatter_dots"): 1.539e9,
+    ("C4", "gemm_gate_up"): 3.477e9,
+    ("C4", "gemm_dX"): 3.393e9,
+}
 
 
 def parse_args():
@@ -38,6 +44,9 @@ def parse_args():
     ap.add_argument("--no-save", action="store_true", help="do not save G/U in the forward (backward recomputes)")
     ap.add_argument("--slab-mb", type=int, default=0)
     ap.add_argument("--verbose", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain 1 GiB device copies (known traffic) so that rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings can be scaled")
     return ap.parse_args()
 
 
@@ -118,6 +127,14 @@ def main():
         lb.lory_merged_ffn_fwd(X, w, Wg, Wu, Wd, cfg.T, Y=Y, G_save=G, U_save=U, workspace=ws_f)
         lb.lory_merged_ffn_bwd(X, w, Wg, Wu, Wd, dY, cfg.T, G_save=G, U_save=U, dX=dX, dWg=dWg, dWu=dWu,
                                dWd=dWd, dw=dw, grad_dtype=gdt, workspace=ws_b)
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
