@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--grad-dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-save", action="store_true", help="do not save G/U in the forward (backward recomputes)")
+    ap.add_argument("--no-merged-save", action="store_true",
+                    help="do not hand the forward's merged parameters to the backward (it re-merges)")
     ap.add_argument("--slab-mb", type=int, default=0)
     ap.add_argument("--verbose", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -116,6 +118,7 @@ def main():
     if not args.no_save:
         G = torch.empty((cfg.tokens, cfg.d_ff), dtype=dt, device=dev)
         U = torch.empty_like(G)
+    Wbar = None if args.no_merged_save else lb.alloc_merged_save(shape)
     dX = torch.empty_like(X)
     dWg = torch.empty(Wg.shape, dtype=gdt, device=dev)
     dWu = torch.empty(Wu.shape, dtype=gdt, device=dev)
@@ -124,9 +127,9 @@ def main():
 
     def step():
         lb.lory_route(X, R, cfg.T, w=w, d_ff=cfg.d_ff)
-        lb.lory_merged_ffn_fwd(X, w, Wg, Wu, Wd, cfg.T, Y=Y, G_save=G, U_save=U, workspace=ws_f)
+        lb.lory_merged_ffn_fwd(X, w, Wg, Wu, Wd, cfg.T, Y=Y, G_save=G, U_save=U, workspace=ws_f, Wbar_save=Wbar)
         lb.lory_merged_ffn_bwd(X, w, Wg, Wu, Wd, dY, cfg.T, G_save=G, U_save=U, dX=dX, dWg=dWg, dWu=dWu,
-                               dWd=dWd, dw=dw, grad_dtype=gdt, workspace=ws_b)
+                               dWd=dWd, dw=dw, grad_dtype=gdt, workspace=ws_b, Wbar_save=Wbar)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -197,7 +200,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} L={cfg.L} T={cfg.T} d={cfg.d} d_ff={cfg.d_ff} E={cfg.E} "
                                f"{cfg.dtype} route+fwd+bwd, grad_dtype={args.grad_dtype}, "
-                               f"save_GU={not args.no_save}",
+                               f"save_GU={not args.no_save}, save_merged={Wbar is not None}",
                    "tokens": cfg.tokens, "segments": cfg.S},
         "gemm_tflops": gemm_tflops,
         "pct_bf16_mfma_peak_gemm_only": 100.0 * gemm_tflops / PEAK_BF16_TFLOPS,

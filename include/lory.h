@@ -110,6 +110,17 @@ int lory_profile_read(lory_kernel_stat *out, int max_out, int *n_out);
 int lory_workspace_bytes(const lory_shape *shape, int pass, size_t *bytes_out);
 
 /*
+ * Bytes of the optional "merged parameters saved for the backward" buffer
+ * (Wbar_save of lory_merged_ffn_fwd / lory_merged_ffn_bwd): 3 * S * d * d_ff
+ * elements of dtype, or 0 when this shape does not support it (LORY_F32, or
+ * more segments than one merge launch handles: S > 256, or S > 128 when
+ * E > 32).  The paper's own implementation keeps the merged FFN parameters of
+ * every segment in memory (Appendix G.2 mentions the cost); here that is an
+ * opt-in trade of memory for one re-merge of the expert stack.  Host-only.
+ */
+int lory_merged_save_bytes(const lory_shape *shape, size_t *bytes_out);
+
+/*
  * Causal segment routing (Section 3.1, Eq. 2; Algorithm 1).
  *   hbar[b,k,:] = (1/T) sum of X[b, kT .. kT+T-1, :]
  *   e[b,k,:]    = softmax(hbar[b,k,:] . R)        (no bias, temperature 1)
@@ -131,13 +142,17 @@ int lory_route(const lory_shape *shape, const void *X, const void *R,
  *     G = X_s Wg_bar, U = X_s Wu_bar, A = G*sigmoid(G) (.) U, Y_s = A Wd_bar
  * in:  X [B, L, d]; w [S, E] fp32 (any rows: lory_route's output, one-hot,
  *      uniform ...); Wg, Wu [E, d, d_ff]; Wd [E, d_ff, d]
- * out: Y [B, L, d]; G_save, U_save [B*L, d_ff] (dtype) or both NULL
- * The merged parameters are never materialised as a whole: they pass through
- * a bounded slab inside the workspace.
+ * out: Y [B, L, d]; G_save, U_save [B*L, d_ff] (dtype) or both NULL;
+ *      Wbar_save: NULL, or lory_merged_save_bytes() bytes that receive the
+ *      merged parameters of all segments, laid out [Wg_bar | Wu_bar | Wd_bar],
+ *      each [S, rows, cols] like one expert matrix (LORY_ERR_SHAPE if the
+ *      shape does not support it).
+ * Without Wbar_save the merged parameters are never materialised as a whole:
+ * they pass through a bounded slab inside the workspace.
  */
 int lory_merged_ffn_fwd(const lory_shape *shape, const void *X, const float *w,
                         const void *Wg, const void *Wu, const void *Wd,
-                        void *Y, void *G_save, void *U_save,
+                        void *Y, void *G_save, void *U_save, void *Wbar_save,
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
@@ -148,7 +163,8 @@ int lory_merged_ffn_fwd(const lory_shape *shape, const void *X, const float *w,
  *   dWg_bar = X^T dG;  dWu_bar = X^T dU;  dX = dG Wg_bar^T + dU Wu_bar^T
  *   dWx[e] = sum_s w[s,e] dWx_bar(s);   dw[s,e] = sum_x <Wx[e], dWx_bar(s)>
  * in:  X, w, Wg, Wu, Wd as for the forward; dY [B, L, d];
- *      G_save, U_save from the forward, or both NULL to recompute them
+ *      G_save, U_save from the forward, or both NULL to recompute them;
+ *      Wbar_save from the forward (same shape, same w), or NULL to re-merge
  * out: dX [B, L, d] (FFN path only; the router path's contribution through
  *      the segment mean is not included); dWg, dWu [E, d, d_ff] and
  *      dWd [E, d_ff, d] in grad_dtype (LORY_F32, or for LORY_BF16 shapes also
@@ -162,6 +178,7 @@ int lory_merged_ffn_fwd(const lory_shape *shape, const void *X, const float *w,
 int lory_merged_ffn_bwd(const lory_shape *shape, const void *X, const float *w,
                         const void *Wg, const void *Wu, const void *Wd,
                         const void *dY, const void *G_save, const void *U_save,
+                        const void *Wbar_save,
                         void *dX, void *dWg, void *dWu, void *dWd,
                         int grad_dtype, int accumulate, float *dw,
                         void *workspace, size_t workspace_bytes, void *stream);

@@ -25,7 +25,7 @@ LORY_F32, LORY_BF16 = 0, 1
 LORY_PASS_FWD, LORY_PASS_BWD = 0, 1
 
 EXPORTS = ("lory_status_string", "lory_version", "lory_set_slab_budget", "lory_profile_enable",
-           "lory_profile_read", "lory_workspace_bytes", "lory_route",
+           "lory_profile_read", "lory_merged_save_bytes", "lory_workspace_bytes", "lory_route",
            "lory_merged_ffn_fwd", "lory_merged_ffn_bwd")
 
 
@@ -72,9 +72,11 @@ def lib() -> ctypes.CDLL:
         L.lory_workspace_bytes.restype = ci
         L.lory_route.argtypes = [sp, vp, vp, vp, vp, vp]
         L.lory_route.restype = ci
-        L.lory_merged_ffn_fwd.argtypes = [sp] + [vp] * 9 + [sz, vp]
+        L.lory_merged_save_bytes.argtypes = [sp, ctypes.POINTER(sz)]
+        L.lory_merged_save_bytes.restype = ci
+        L.lory_merged_ffn_fwd.argtypes = [sp] + [vp] * 10 + [sz, vp]
         L.lory_merged_ffn_fwd.restype = ci
-        L.lory_merged_ffn_bwd.argtypes = [sp] + [vp] * 12 + [ci, ci, vp, vp, sz, vp]
+        L.lory_merged_ffn_bwd.argtypes = [sp] + [vp] * 13 + [ci, ci, vp, vp, sz, vp]
         L.lory_merged_ffn_bwd.restype = ci
         _lib = L
     return _lib
@@ -144,6 +146,18 @@ def lory_workspace_bytes(shape: LoryShape, which_pass: int) -> int:
     return out.value
 
 
+def lory_merged_save_bytes(shape: LoryShape) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().lory_merged_save_bytes(ctypes.byref(shape), ctypes.byref(out)), "lory_merged_save_bytes")
+    return out.value
+
+
+def alloc_merged_save(shape: LoryShape, device="cuda") -> Optional[torch.Tensor]:
+    """Buffer for the merged parameters saved by the forward, or None if the shape has no support."""
+    n = lory_merged_save_bytes(shape)
+    return torch.empty(n, dtype=torch.uint8, device=device) if n else None
+
+
 def alloc_workspace(shape: LoryShape, which_pass: int, device="cuda") -> torch.Tensor:
     n = lory_workspace_bytes(shape, which_pass)
     return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
@@ -174,7 +188,8 @@ def lory_route(X: torch.Tensor, R: torch.Tensor, T: int, w: Optional[torch.Tenso
 def lory_merged_ffn_fwd(X: torch.Tensor, w: torch.Tensor, Wg: torch.Tensor, Wu: torch.Tensor,
                         Wd: torch.Tensor, T: int, Y: Optional[torch.Tensor] = None,
                         G_save: Optional[torch.Tensor] = None, U_save: Optional[torch.Tensor] = None,
-                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+                        workspace: Optional[torch.Tensor] = None,
+                        Wbar_save: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Y = merged SwiGLU FFN of every segment; optionally saves G and U."""
     E, d, d_ff = Wg.shape
     shape = _shape_from(X, T, d_ff, E)
@@ -190,7 +205,7 @@ def lory_merged_ffn_fwd(X: torch.Tensor, w: torch.Tensor, Wg: torch.Tensor, Wu: 
     if workspace is None:
         workspace = alloc_workspace(shape, LORY_PASS_FWD, X.device)
     _check(lib().lory_merged_ffn_fwd(ctypes.byref(shape), _ptr(X), _ptr(w), _ptr(Wg), _ptr(Wu), _ptr(Wd),
-                                     _ptr(Y), _ptr(G_save), _ptr(U_save), _ptr(workspace),
+                                     _ptr(Y), _ptr(G_save), _ptr(U_save), _ptr(Wbar_save), _ptr(workspace),
                                      workspace.numel(), _stream()), "lory_merged_ffn_fwd")
     return Y
 
@@ -201,7 +216,8 @@ def lory_merged_ffn_bwd(X: torch.Tensor, w: torch.Tensor, Wg: torch.Tensor, Wu: 
                         dX: Optional[torch.Tensor] = None, dWg: Optional[torch.Tensor] = None,
                         dWu: Optional[torch.Tensor] = None, dWd: Optional[torch.Tensor] = None,
                         dw: Optional[torch.Tensor] = None, grad_dtype: Optional[torch.dtype] = None,
-                        accumulate: bool = False, workspace: Optional[torch.Tensor] = None
+                        accumulate: bool = False, workspace: Optional[torch.Tensor] = None,
+                        Wbar_save: Optional[torch.Tensor] = None
                         ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor]:
     """Returns (dX, dWg, dWu, dWd, dw)."""
     E, d, d_ff = Wg.shape
@@ -226,7 +242,7 @@ def lory_merged_ffn_bwd(X: torch.Tensor, w: torch.Tensor, Wg: torch.Tensor, Wu: 
     if workspace is None:
         workspace = alloc_workspace(shape, LORY_PASS_BWD, X.device)
     _check(lib().lory_merged_ffn_bwd(ctypes.byref(shape), _ptr(X), _ptr(w), _ptr(Wg), _ptr(Wu), _ptr(Wd),
-                                     _ptr(dY), _ptr(G_save), _ptr(U_save), _ptr(dX), _ptr(dWg), _ptr(dWu),
+                                     _ptr(dY), _ptr(G_save), _ptr(U_save), _ptr(Wbar_save), _ptr(dX), _ptr(dWg), _ptr(dWu),
                                      _ptr(dWd), _dtype_code(grad_dtype), int(bool(accumulate)), _ptr(dw),
                                      _ptr(workspace), workspace.numel(), _stream()),
            "lory_merged_ffn_bwd")

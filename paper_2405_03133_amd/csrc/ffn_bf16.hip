@@ -131,9 +131,9 @@ hipError_t merge(hipStream_t st, const float *w, int S, int E, const bf *stack, 
 
 // Gate/up projections of one d_ff column block for a chunk of segments.
 hipError_t gate_up_block(hipStream_t st, const Dims &m, int S, const bf *X, const float *w, const bf *Wg,
-                         const bf *Wu, int n0, int nf, bf *slab, bf *G, bf *U, bf *Act)
+                         const bf *Wu, int n0, int nf, bf *slab, bf *G, bf *U, bf *Act, bf *slab_up = nullptr)
 {
-    bf *sg = slab, *su = slab + (size_t)S * m.d * nf;
+    bf *sg = slab, *su = slab_up ? slab_up : slab + (size_t)S * m.d * nf;
     const Rect rc = rect(m.D, m.dff, 0, m.d, n0, nf);
     hipError_t e;
     if ((e = merge(st, w, S, m.E, Wg, rc, sg)) != hipSuccess) return e;
@@ -170,6 +170,13 @@ int set_slab_budget(size_t bytes)
     return LORY_OK;
 }
 
+size_t bf16_merged_save_bytes(const Dims &m)
+{
+    const Plan p = make_plan(m);
+    if (m.S > p.Sc) return 0;  // more segments than one merge launch handles
+    return (size_t)3 * m.S * m.D * 2;
+}
+
 size_t bf16_workspace_bytes(const Dims &m, int pass)
 {
     const Plan p = make_plan(m);
@@ -179,9 +186,14 @@ size_t bf16_workspace_bytes(const Dims &m, int pass)
 }
 
 int bf16_ffn_fwd(const Dims &m, const void *Xv, const float *w, const void *Wgv, const void *Wuv,
-                 const void *Wdv, void *Yv, void *Gv, void *Uv, void *ws, hipStream_t st)
+                 const void *Wdv, void *Yv, void *Gv, void *Uv, void *Wbarv, void *ws, hipStream_t st)
 {
-    const Plan pl = make_plan(m);
+    Plan pl = make_plan(m);
+    bf *Wbar = (bf *)Wbarv;  // [Wg_bar | Wu_bar | Wd_bar], each [S][rows][cols]; doubles as the slab
+    if (Wbar) {
+        pl.nf_fwd = m.dff;
+        pl.jf_fwd = m.d;
+    }
     const bf *X = (const bf *)Xv, *Wg = (const bf *)Wgv, *Wu = (const bf *)Wuv, *Wd = (const bf *)Wdv;
     bf *Y = (bf *)Yv, *G = (bf *)Gv, *U = (bf *)Uv;
     bf *Act = (bf *)ws;
@@ -197,15 +209,20 @@ int bf16_ffn_fwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
         // gate / up projections + SwiGLU, one d_ff column block at a time
         for (int n0 = 0; n0 < m.dff; n0 += pl.nf_fwd) {
             const int nf = (m.dff - n0 < pl.nf_fwd) ? (m.dff - n0) : pl.nf_fwd;
-            LORY_TRY(gate_up_block(st, m, S, Xc, wc, Wg, Wu, n0, nf, slab, Gc, Uc, Act));
+            if (Wbar)
+                LORY_TRY(gate_up_block(st, m, S, Xc, wc, Wg, Wu, n0, nf, Wbar, Gc, Uc, Act,
+                                       Wbar + (size_t)m.S * m.D));
+            else
+                LORY_TRY(gate_up_block(st, m, S, Xc, wc, Wg, Wu, n0, nf, slab, Gc, Uc, Act));
         }
         // down projection, one block of output columns at a time
         for (int j0 = 0; j0 < m.d; j0 += pl.jf_fwd) {
             const int jf = (m.d - j0 < pl.jf_fwd) ? (m.d - j0) : pl.jf_fwd;
-            LORY_TRY(merge(st, wc, S, m.E, Wd, rect(m.D, m.d, 0, m.dff, j0, jf), slab));
+            bf *sd = Wbar ? Wbar + (size_t)2 * m.S * m.D : slab;
+            LORY_TRY(merge(st, wc, S, m.E, Wd, rect(m.D, m.d, 0, m.dff, j0, jf), sd));
             Params p = {};
             p.A[0] = Act; p.a_batch[0] = TF; p.lda[0] = m.dff;
-            p.B[0] = slab; p.b_batch[0] = (long)m.dff * jf; p.ldb[0] = jf;
+            p.B[0] = sd; p.b_batch[0] = (long)m.dff * jf; p.ldb[0] = jf;
             p.M = m.T; p.N = jf; p.K = m.dff; p.batches = S;
             EpiStore epi = {Y + (size_t)s0 * TD + j0, TD, m.d};
             prof::Range r(st, prof::kGemmDown, gemm_flops(p, 1, 1),
@@ -217,10 +234,14 @@ int bf16_ffn_fwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
 }
 
 int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv, const void *Wuv,
-                 const void *Wdv, const void *dYv, const void *Gv, const void *Uv, void *dXv,
-                 void *dWg, void *dWu, void *dWd, int grad_dtype, int accumulate, float *dw, void *ws,
-                 hipStream_t st)
+                 const void *Wdv, const void *dYv, const void *Gv, const void *Uv, const void *Wbarv,
+                 void *dXv, void *dWg, void *dWu, void *dWd, int grad_dtype, int accumulate, float *dw,
+                 void *ws, hipStream_t st)
 {
+    // saved merged parameters [Wg_bar | Wu_bar | Wd_bar]: no re-merge, the GEMMs read them in place
+    const bf *Wbar = (const bf *)Wbarv;
+    const bf *Wbar_g = Wbar, *Wbar_u = Wbar ? Wbar + (size_t)m.S * m.D : nullptr;
+    const bf *Wbar_d = Wbar ? Wbar + (size_t)2 * m.S * m.D : nullptr;
     const Plan pl = make_plan(m);
     const bf *X = (const bf *)Xv, *Wg = (const bf *)Wgv, *Wu = (const bf *)Wuv, *Wd = (const bf *)Wdv;
     const bf *dY = (const bf *)dYv, *G = (const bf *)Gv, *U = (const bf *)Uv;
@@ -267,11 +288,13 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
             const Rect cols_f = rect(m.D, m.dff, 0, m.d, n0, nf);    // columns n0.. of Wg/Wu [d, d_ff]
 
             // dA = dY Wd_bar^T for these d_ff columns, then the SwiGLU backward pass: dG, dU, A
-            LORY_TRY(merge(st, wc, S, m.E, Wd, rows_d, s_md));
+            if (!Wbar) LORY_TRY(merge(st, wc, S, m.E, Wd, rows_d, s_md));
             {
                 Params p = {};
                 p.A[0] = dYc; p.a_batch[0] = TD; p.lda[0] = m.d;
-                p.B[0] = s_md; p.b_batch[0] = (long)nf * m.d; p.ldb[0] = m.d;
+                p.B[0] = Wbar ? Wbar_d + (size_t)n0 * m.d : s_md;
+                p.b_batch[0] = Wbar ? m.D : (long)nf * m.d;
+                p.ldb[0] = m.d;
                 p.M = m.T; p.N = nf; p.K = m.d; p.batches = S;
                 EpiStore epi = {dG + n0, TF, m.dff};  // dA parks in the dG buffer
                 {
@@ -336,13 +359,17 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
             const size_t blk = (size_t)S * kf * m.dff;
             bf *s_g = slab, *s_u = slab + blk;
             const Rect rows = rect(m.D, m.dff, k0, kf, 0, m.dff);
-            LORY_TRY(merge(st, wc, S, m.E, Wg, rows, s_g));
-            LORY_TRY(merge(st, wc, S, m.E, Wu, rows, s_u));
+            if (!Wbar) {
+                LORY_TRY(merge(st, wc, S, m.E, Wg, rows, s_g));
+                LORY_TRY(merge(st, wc, S, m.E, Wu, rows, s_u));
+            }
             Params p = {};
             p.A[0] = dG; p.a_batch[0] = TF; p.lda[0] = m.dff;
             p.A[1] = dU; p.a_batch[1] = TF; p.lda[1] = m.dff;
-            p.B[0] = s_g; p.b_batch[0] = (long)kf * m.dff; p.ldb[0] = m.dff;
-            p.B[1] = s_u; p.b_batch[1] = (long)kf * m.dff; p.ldb[1] = m.dff;
+            p.B[0] = Wbar ? Wbar_g + (size_t)k0 * m.dff : s_g;
+            p.B[1] = Wbar ? Wbar_u + (size_t)k0 * m.dff : s_u;
+            p.b_batch[0] = p.b_batch[1] = Wbar ? m.D : (long)kf * m.dff;
+            p.ldb[0] = p.ldb[1] = m.dff;
             p.M = m.T; p.N = kf; p.K = m.dff; p.batches = S;
             EpiStore epi = {dX + (size_t)s0 * TD + k0, TD, m.d};
             prof::Range r(st, prof::kGemmDX, gemm_flops(p, 1, 2),

@@ -56,6 +56,16 @@ int lory_profile_read(lory_kernel_stat *out, int max_out, int *n_out)
     return lory::prof::read(out, max_out, n_out);
 }
 
+int lory_merged_save_bytes(const lory_shape *shape, size_t *bytes_out)
+{
+    if (!bytes_out) return LORY_ERR_NULL;
+    const int rc = check_shape(shape);
+    if (rc != LORY_OK) return rc;
+    const Dims m = lory::make_dims(*shape);
+    *bytes_out = (m.dtype == LORY_BF16) ? lory::bf16_merged_save_bytes(m) : 0;
+    return LORY_OK;
+}
+
 int lory_workspace_bytes(const lory_shape *shape, int pass, size_t *bytes_out)
 {
     if (!bytes_out) return LORY_ERR_NULL;
@@ -85,15 +95,21 @@ int lory_route(const lory_shape *shape, const void *X, const void *R, float *w, 
 
 int lory_merged_ffn_fwd(const lory_shape *shape, const void *X, const float *w, const void *Wg,
                         const void *Wu, const void *Wd, void *Y, void *G_save, void *U_save,
-                        void *workspace, size_t workspace_bytes, void *stream)
+                        void *Wbar_save, void *workspace, size_t workspace_bytes, void *stream)
 {
     const int rc = check_shape(shape);
     if (rc != LORY_OK) return rc;
     if (!X || !w || !Wg || !Wu || !Wd || !Y || !workspace) return LORY_ERR_NULL;
     if ((G_save == nullptr) != (U_save == nullptr)) return LORY_ERR_NULL;
     if (!aligned16(X) || !aligned16(w) || !aligned16(Wg) || !aligned16(Wu) || !aligned16(Wd) ||
-        !aligned16(Y) || !aligned16(G_save) || !aligned16(U_save) || !aligned16(workspace))
+        !aligned16(Y) || !aligned16(G_save) || !aligned16(U_save) || !aligned16(Wbar_save) ||
+        !aligned16(workspace))
         return LORY_ERR_ALIGN;
+    if (Wbar_save) {
+        size_t sb = 0;
+        lory_merged_save_bytes(shape, &sb);
+        if (sb == 0) return LORY_ERR_SHAPE;
+    }
     size_t need = 0;
     lory_workspace_bytes(shape, LORY_PASS_FWD, &need);
     if (workspace_bytes < need) return LORY_ERR_WORKSPACE;
@@ -103,12 +119,13 @@ int lory_merged_ffn_fwd(const lory_shape *shape, const void *X, const float *w, 
         return lory::f32_ffn_fwd(m, (const float *)X, w, (const float *)Wg, (const float *)Wu,
                                  (const float *)Wd, (float *)Y, (float *)G_save, (float *)U_save,
                                  workspace, st);
-    return lory::bf16_ffn_fwd(m, X, w, Wg, Wu, Wd, Y, G_save, U_save, workspace, st);
+    return lory::bf16_ffn_fwd(m, X, w, Wg, Wu, Wd, Y, G_save, U_save, Wbar_save, workspace, st);
 }
 
 int lory_merged_ffn_bwd(const lory_shape *shape, const void *X, const float *w, const void *Wg,
                         const void *Wu, const void *Wd, const void *dY, const void *G_save,
-                        const void *U_save, void *dX, void *dWg, void *dWu, void *dWd,
+                        const void *U_save, const void *Wbar_save, void *dX, void *dWg, void *dWu,
+                        void *dWd,
                         int grad_dtype, int accumulate, float *dw, void *workspace,
                         size_t workspace_bytes, void *stream)
 {
@@ -121,10 +138,16 @@ int lory_merged_ffn_bwd(const lory_shape *shape, const void *X, const float *w, 
     if (shape->dtype == LORY_F32 && grad_dtype != LORY_F32) return LORY_ERR_DTYPE;
     if (accumulate != 0 && accumulate != 1) return LORY_ERR_SHAPE;
     if (!aligned16(X) || !aligned16(w) || !aligned16(Wg) || !aligned16(Wu) || !aligned16(Wd) ||
-        !aligned16(dY) || !aligned16(G_save) || !aligned16(U_save) || !aligned16(dX) ||
+        !aligned16(dY) || !aligned16(G_save) || !aligned16(U_save) || !aligned16(Wbar_save) ||
+        !aligned16(dX) ||
         !aligned16(dWg) || !aligned16(dWu) || !aligned16(dWd) || !aligned16(dw) ||
         !aligned16(workspace))
         return LORY_ERR_ALIGN;
+    if (Wbar_save) {
+        size_t sb = 0;
+        lory_merged_save_bytes(shape, &sb);
+        if (sb == 0) return LORY_ERR_SHAPE;
+    }
     size_t need = 0;
     lory_workspace_bytes(shape, LORY_PASS_BWD, &need);
     if (workspace_bytes < need) return LORY_ERR_WORKSPACE;
@@ -135,8 +158,8 @@ int lory_merged_ffn_bwd(const lory_shape *shape, const void *X, const float *w, 
                                  (const float *)Wd, (const float *)dY, (const float *)G_save,
                                  (const float *)U_save, (float *)dX, (float *)dWg, (float *)dWu,
                                  (float *)dWd, accumulate, dw, workspace, st);
-    return lory::bf16_ffn_bwd(m, X, w, Wg, Wu, Wd, dY, G_save, U_save, dX, dWg, dWu, dWd, grad_dtype,
-                              accumulate, dw, workspace, st);
+    return lory::bf16_ffn_bwd(m, X, w, Wg, Wu, Wd, dY, G_save, U_save, Wbar_save, dX, dWg, dWu, dWd,
+                              grad_dtype, accumulate, dw, workspace, st);
 }
 
 }  // extern "C"

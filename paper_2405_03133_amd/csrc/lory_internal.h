@@ -77,11 +77,13 @@ int f32_ffn_bwd(const Dims &m, const float *X, const float *w, const float *Wg, 
 // ---- bf16 path (ffn_bf16.hip)
 int set_slab_budget(size_t bytes);
 size_t bf16_workspace_bytes(const Dims &m, int pass);
+size_t bf16_merged_save_bytes(const Dims &m);
 int bf16_ffn_fwd(const Dims &m, const void *X, const float *w, const void *Wg, const void *Wu,
-                 const void *Wd, void *Y, void *G_save, void *U_save, void *ws, hipStream_t st);
+                 const void *Wd, void *Y, void *G_save, void *U_save, void *Wbar_save, void *ws,
+                 hipStream_t st);
 int bf16_ffn_bwd(const Dims &m, const void *X, const float *w, const void *Wg, const void *Wu,
                  const void *Wd, const void *dY, const void *G_save, const void *U_save,
-                 void *dX, void *dWg, void *dWu, void *dWd, int grad_dtype, int accumulate,
-                 float *dw, void *ws, hipStream_t st);
+                 const void *Wbar_save, void *dX, void *dWg, void *dWu, void *dWd, int grad_dtype,
+                 int accumulate, float *dw, void *ws, hipStream_t st);
 
 }  // namespace lory

@@ -75,12 +75,18 @@ def test_workspace_query_and_ffn_validation(dtype):
     sp = ctypes.byref(s)
     F = FAKE
     # forward: NULL, mismatched save pair, alignment, short workspace
-    assert L.lory_merged_ffn_fwd(sp, None, F, F, F, F, F, None, None, F, need_f, None) == lb.LORY_ERR_NULL
-    assert L.lory_merged_ffn_fwd(sp, F, F, F, F, F, F, F, None, F, need_f, None) == lb.LORY_ERR_NULL
-    assert L.lory_merged_ffn_fwd(sp, F, F, F, F + 8, F, F, None, None, F, need_f, None) == lb.LORY_ERR_ALIGN
-    assert L.lory_merged_ffn_fwd(sp, F, F, F, F, F, F, None, None, F, need_f - 1, None) == lb.LORY_ERR_WORKSPACE
+    assert L.lory_merged_ffn_fwd(sp, None, F, F, F, F, F, None, None, None, F, need_f, None) == lb.LORY_ERR_NULL
+    assert L.lory_merged_ffn_fwd(sp, F, F, F, F, F, F, F, None, None, F, need_f, None) == lb.LORY_ERR_NULL
+    assert L.lory_merged_ffn_fwd(sp, F, F, F, F + 8, F, F, None, None, None, F, need_f, None) == lb.LORY_ERR_ALIGN
+    assert L.lory_merged_ffn_fwd(sp, F, F, F, F, F, F, None, None, None, F, need_f - 1, None) == lb.LORY_ERR_WORKSPACE
+    save = lb.lory_merged_save_bytes(s)
+    if dtype == lb.LORY_F32:
+        assert save == 0
+        assert L.lory_merged_ffn_fwd(sp, F, F, F, F, F, F, None, None, F, F, need_f, None) == lb.LORY_ERR_SHAPE
+    else:
+        assert save == 3 * 8 * 64 * 256 * 2
     # backward
-    args = [F] * 12
+    args = [F] * 8 + [None] + [F] * 4   # ..., U_save, Wbar_save = NULL, dX, dWg, dWu, dWd
     assert L.lory_merged_ffn_bwd(sp, *args, lb.LORY_F32, 0, None, F, need_b, None) == lb.LORY_ERR_NULL
     assert L.lory_merged_ffn_bwd(sp, *args, 9, 0, F, F, need_b, None) == lb.LORY_ERR_DTYPE
     assert L.lory_merged_ffn_bwd(sp, *args, lb.LORY_F32, 2, F, F, need_b, None) == lb.LORY_ERR_SHAPE
@@ -88,5 +94,5 @@ def test_workspace_query_and_ffn_validation(dtype):
     if dtype == lb.LORY_F32:
         assert L.lory_merged_ffn_bwd(sp, *args, lb.LORY_BF16, 0, F, F, need_b, None) == lb.LORY_ERR_DTYPE
     bad = list(args)
-    bad[9] = F + 2
+    bad[10] = F + 2
     assert L.lory_merged_ffn_bwd(sp, *bad, lb.LORY_F32, 0, F, F, need_b, None) == lb.LORY_ERR_ALIGN

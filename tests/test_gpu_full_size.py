@@ -1,5 +1,6 @@
 """Parity at the benchmark's full size (headline configuration, launch
-configuration of bench.py: default slab budget, saved G/U, bf16 gradients),
+configuration of bench.py: default slab budget, saved G/U and merged
+parameters, bf16 gradients),
 checked on sampled outputs that the fp64 oracle can compute one by one:
 
   * routing weights: all of them (the oracle's route is cheap);
@@ -45,9 +46,12 @@ def test_full_size_sampled(name):
     w = lb.lory_route(dev["X"], dev["R"], cfg.T, d_ff=cfg.d_ff)
     G = torch.empty((cfg.tokens, cfg.d_ff), dtype=torch.bfloat16, device="cuda")
     U = torch.empty_like(G)
-    Y = lb.lory_merged_ffn_fwd(dev["X"], w, dev["Wg"], dev["Wu"], dev["Wd"], cfg.T, G_save=G, U_save=U)
+    Wbar = lb.alloc_merged_save(lb.make_shape(cfg.B, cfg.L, cfg.T, cfg.d, cfg.d_ff, cfg.E, torch.bfloat16))
+    Y = lb.lory_merged_ffn_fwd(dev["X"], w, dev["Wg"], dev["Wu"], dev["Wd"], cfg.T, G_save=G, U_save=U,
+                               Wbar_save=Wbar)
     dX, dWg, dWu, dWd, dw = lb.lory_merged_ffn_bwd(dev["X"], w, dev["Wg"], dev["Wu"], dev["Wd"], dev["dY"],
-                                                   cfg.T, G_save=G, U_save=U, grad_dtype=torch.bfloat16)
+                                                   cfg.T, G_save=G, U_save=U, grad_dtype=torch.bfloat16,
+                                                   Wbar_save=Wbar)
     torch.cuda.synchronize()
     w_h = host(w)
 

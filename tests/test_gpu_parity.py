@@ -36,7 +36,7 @@ def host(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def run_layer(cfg, t, w_override=None, save=True, grad_dtype=torch.float32):
+def run_layer(cfg, t, w_override=None, save=True, grad_dtype=torch.float32, merged_save=False):
     """route -> fwd -> bwd on the GPU through the C ABI; returns numpy float64."""
     print(f"[gpu] {cfg}", flush=True)
     X, R = to_dev(t["X"], cfg), to_dev(t["R"], cfg)
@@ -49,9 +49,13 @@ def run_layer(cfg, t, w_override=None, save=True, grad_dtype=torch.float32):
     if save:
         G = torch.empty((cfg.tokens, cfg.d_ff), dtype=X.dtype, device="cuda")
         U = torch.empty_like(G)
-    Y = lb.lory_merged_ffn_fwd(X, w_used, Wg, Wu, Wd, cfg.T, G_save=G, U_save=U)
+    Wbar = None
+    if merged_save:
+        Wbar = lb.alloc_merged_save(lb.make_shape(cfg.B, cfg.L, cfg.T, cfg.d, cfg.d_ff, cfg.E, X.dtype))
+        assert Wbar is not None
+    Y = lb.lory_merged_ffn_fwd(X, w_used, Wg, Wu, Wd, cfg.T, G_save=G, U_save=U, Wbar_save=Wbar)
     dX, dWg, dWu, dWd, dw = lb.lory_merged_ffn_bwd(X, w_used, Wg, Wu, Wd, dY, cfg.T, G_save=G, U_save=U,
-                                                   grad_dtype=grad_dtype)
+                                                   grad_dtype=grad_dtype, Wbar_save=Wbar)
     torch.cuda.synchronize()
     out = {"w": host(w), "hbar": host(hbar), "Y": host(Y), "dX": host(dX), "dWg": host(dWg),
            "dWu": host(dWu), "dWd": host(dWd), "dw": host(dw), "w_used": host(w_used)}
@@ -219,3 +223,25 @@ def test_bf16_onehot_and_determinism(default_budget):
     compare(cfg, a, ref, ALL, TOL["bf16"])
     for key in ALL:
         assert np.array_equal(a[key], b[key]), key
+
+
+@pytest.mark.parametrize("idx", [0, 6])
+def test_bf16_saved_merged_parameters_match_remerge(idx, default_budget):
+    """The forward may hand its merged parameters to the backward; results are those of the
+    re-merging path (same values, same accumulation order), and within tolerance of the oracle."""
+    cfg, budget = BF16_CASES[idx]
+    lb.lory_set_slab_budget(budget)
+    t = make_inputs(cfg, structured=True)
+    a = run_layer(cfg, t, merged_save=True)
+    b = run_layer(cfg, t, merged_save=False)
+    ref = oracle_layer(cfg, t, a["w_used"])
+    compare(cfg, a, ref, ALL, TOL["bf16"])
+    for key in ALL:
+        assert np.array_equal(a[key], b[key]), key
+
+
+def test_merged_save_unsupported_shapes_are_rejected():
+    shape = lb.make_shape(5, 3840, 64, 64, 128, 64, torch.bfloat16)   # S = 300 > 128 at E = 64
+    assert lb.lory_merged_save_bytes(shape) == 0
+    shape32 = lb.make_shape(2, 512, 128, 64, 256, 4, torch.float32)
+    assert lb.lory_merged_save_bytes(shape32) == 0
