@@ -70,7 +70,7 @@ const char *lory_version(void);
  * Tuning knob (process-global, host-only): upper bound in bytes for the
  * transient slab through which merged parameters and per-segment weight
  * gradients pass (Eq. 2's theta_bar is produced and consumed block by block).
- * Default 4 GiB: on MI355X large blocks (few, long launches that fill all 256
+ * Default 6 GiB: on MI355X large blocks (few, long launches that fill all 256
  * CUs) measured faster than blocks sized for the 256 MB memory-side cache; the
  * LORY_SLAB_MB environment variable sets the initial value.  Changes what
  * lory_workspace_bytes reports, so set it before sizing a workspace.

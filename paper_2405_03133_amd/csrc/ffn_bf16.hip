@@ -8,7 +8,7 @@
 // per-segment token GEMMs that consume the slab.  The backward additionally
 // produces per-segment weight-gradient slabs that the scatter kernel folds
 // into the E expert gradients and into the router-weight gradients at once.
-// The slab budget (default 4 GiB) trades workspace for launch size: blocks large enough to
+// The slab budget (default 6 GiB) trades workspace for launch size: blocks large enough to
 // fill all 256 CUs several times over measured faster than cache-sized blocks.
 #include "lory_internal.h"
 
@@ -35,7 +35,7 @@ size_t g_slab_budget = 0;  // 0 = not initialised yet
 size_t slab_budget_bytes()
 {
     if (g_slab_budget == 0) {
-        size_t mb = 4096;
+        size_t mb = 6144;
         if (const char *env = getenv("LORY_SLAB_MB")) {
             const long v = atol(env);
             if (v >= 1 && v <= 16384) mb = (size_t)v;

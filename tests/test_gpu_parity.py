@@ -175,7 +175,7 @@ BF16_CASES = [
 @pytest.fixture
 def default_budget():
     yield
-    lb.lory_set_slab_budget(4096 << 20)
+    lb.lory_set_slab_budget(6144 << 20)
 
 
 @pytest.mark.parametrize("cfg,budget", BF16_CASES, ids=lambda v: v.name if isinstance(v, LoryConfig) else str(v))
