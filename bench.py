@@ -24,12 +24,14 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 
 # HBM bytes per launch (average over the launches of a step) from the rocprofv3 --pmc runs summarised in
 # profiles/hbm_traffic_C4_fwd_bwd.txt: FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the factors that make a plain
-# 1 GiB device copy read 1 GiB and write 1 GiB.  Only valid for the default launch configuration.
+# 1 GiB device copy read 1 GiB and write 1 GiB.  Only valid for the default launch configuration (G/U and
+# merged parameters saved, default slab budget).
 TRAFFIC_BYTES = {
-    ("C4", "merge"): 1.899e9,
-    ("C4", "scatter_dots"): 1.539e9,
+    ("C4", "merge"): 2.215e9,
+    ("C4", "scatter_dots"): 3.009e9,
     ("C4", "gemm_gate_up"): 3.477e9,
     ("C4", "gemm_dX"): 3.393e9,
+    ("C4", "gemm_dW_gate_up"): 6.040e9,
 }
 
 
@@ -181,7 +183,8 @@ def main():
             roofline = {"kernel": dominant, "bound": "hbm", "achieved": kd["gbs"], "peak": PEAK_HBM_GBS,
                         "unit": "GB/s", "frac": kd["gbs"] / PEAK_HBM_GBS}
         roofline["avg_launch_us"] = kd["avg_us"]
-        roofline["traffic"] = TRAFFIC_BYTES.get((args.config, dominant))
+        default_launch = not (args.no_save or args.no_merged_save or args.slab_mb or args.grad_dtype != "bf16")
+        roofline["traffic"] = TRAFFIC_BYTES.get((args.config, dominant)) if default_launch else None
 
     gemm_tflops = cfg.gemm_flops(True) / (ms_per_step * 1e-3) / 1e12
     all_tflops = (cfg.gemm_flops(True) + cfg.merge_flops(4)) / (ms_per_step * 1e-3) / 1e12
