@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the Lory merged-MoE-FFN hot path on one MI355X.
 
-One step = lory_route -> lory_merged_ffn_fwd -> lory_merged_ffn_bwd over one
-batch of synthetic hidden states (inputs already resident in HBM).  Prints ONE
+One step = lory_route -> lory_merged_ffn_fwd -> lory_merged_ffn_bwd ->
+lory_route_bwd (the whole layer and its gradient) over one batch of synthetic
+hidden states (inputs already resident in HBM).  Prints ONE
 JSON line: whole-job tokens/s, the roofline figures of the dominant kernel
 class (timed with HIP events inside the library on the stream it launches on),
 and the CPU oracle timed on a bounded sample of the same workload.
@@ -55,7 +56,7 @@ def parse_args():
 
 
 def cpu_baseline(cfg, verbose=False):
-    """Time the fp64 oracle (route + fwd + bwd) on two segments of the same shape."""
+    """Time the fp64 oracle (route + fwd + bwd + router bwd) on a few segments of the same shape."""
     import numpy as np
     from oracle import lory_oracle as orc
     from paper_2405_03133_amd.inputs import make_inputs
@@ -69,13 +70,14 @@ def cpu_baseline(cfg, verbose=False):
     r = orc.route(t64["X"], t64["R"], sample.T)
     f = orc.ffn_fwd(t64["X"], r["w"], t64["Wg"], t64["Wu"], t64["Wd"], sample.T)
     g = orc.ffn_bwd(t64["X"], r["w"], t64["Wg"], t64["Wu"], t64["Wd"], t64["dY"], sample.T)
+    rb = orc.route_bwd(t64["X"], t64["R"], g["dw"], sample.T)
     dt = time.perf_counter() - t0
-    del f, g
+    del f, g, rb
     if verbose:
         print(f"[cpu] oracle {sample.tokens} tokens in {dt:.2f} s", file=sys.stderr)
     return {"value": sample.tokens / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
             "sample": f"{n_seg} segments of T={cfg.T} tokens at the full d={cfg.d}, d_ff={cfg.d_ff}, E={cfg.E} "
-                      f"(route+fwd+bwd, fp64, {dt:.1f} s)"}
+                      f"(route+fwd+bwd+route_bwd, fp64, {dt:.1f} s)"}
 
 
 def main():
@@ -126,12 +128,15 @@ def main():
     dWu = torch.empty(Wu.shape, dtype=gdt, device=dev)
     dWd = torch.empty(Wd.shape, dtype=gdt, device=dev)
     dw = torch.empty_like(w)
+    hbar = torch.empty((cfg.S, cfg.d), dtype=torch.float32, device=dev)
+    dR = torch.empty((cfg.d, cfg.E), dtype=torch.float32, device=dev)
 
     def step():
-        lb.lory_route(X, R, cfg.T, w=w, d_ff=cfg.d_ff)
+        lb.lory_route(X, R, cfg.T, w=w, hbar=hbar, d_ff=cfg.d_ff)
         lb.lory_merged_ffn_fwd(X, w, Wg, Wu, Wd, cfg.T, Y=Y, G_save=G, U_save=U, workspace=ws_f, Wbar_save=Wbar)
         lb.lory_merged_ffn_bwd(X, w, Wg, Wu, Wd, dY, cfg.T, G_save=G, U_save=U, dX=dX, dWg=dWg, dWu=dWu,
                                dWd=dWd, dw=dw, grad_dtype=gdt, workspace=ws_b, Wbar_save=Wbar)
+        lb.lory_route_bwd(R, w, hbar, dw, dX, cfg.T, dR=dR, d_ff=cfg.d_ff)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -202,7 +207,7 @@ def main():
         "dtype": cfg.dtype,
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} L={cfg.L} T={cfg.T} d={cfg.d} d_ff={cfg.d_ff} E={cfg.E} "
-                               f"{cfg.dtype} route+fwd+bwd, grad_dtype={args.grad_dtype}, "
+                               f"{cfg.dtype} route+fwd+bwd+route_bwd, grad_dtype={args.grad_dtype}, "
                                f"save_GU={not args.no_save}, save_merged={Wbar is not None}",
                    "tokens": cfg.tokens, "segments": cfg.S},
         "gemm_tflops": gemm_tflops,

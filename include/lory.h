@@ -128,12 +128,33 @@ int lory_merged_save_bytes(const lory_shape *shape, size_t *bytes_out);
  *   w[b,k,:]    = e[b,k-1,:]     for 1 <= k < N   (shift by one segment)
  * in:  X [B, L, d] (dtype), R [d, E] (dtype)
  * out: w [B*N, E] fp32, rows sum to 1; hbar_opt [B*N, d] fp32 or NULL.
- * The stop gradient on the first segment only matters for a router
- * backward, which is not part of this entry point.  Mean, logits and softmax
+ * The stop gradient on the first segment only matters for the router
+ * backward (lory_route_bwd).  Mean, logits and softmax
  * are computed in fp32 for both dtypes.  Needs no workspace.
  */
 int lory_route(const lory_shape *shape, const void *X, const void *R,
                float *w, float *hbar_opt, void *stream);
+
+/*
+ * Router backward: the chain rule through lory_route (Section 3.1, Eq. 2),
+ * with the stop gradient Algorithm 1 puts on the first segment's own routing
+ * weights.  With e[b,j] = softmax(hbar[b,j] R) (read back as w[b,j+1]):
+ *   de[b,j] = dw[b,j+1] for j < N-1, and 0 for the last segment of a sequence
+ *             (dw[b,0] is not used: w[b,0] is a stopped copy of e[b,0])
+ *   dz[b,j] = e[b,j] * (de[b,j] - <e[b,j], de[b,j]>)
+ *   dR      = sum over all segments of hbar[b,j]^T dz[b,j]
+ *   dX[b, jT+t, :] += (dz[b,j] R^T) / T          for every token t of segment j
+ * in:     R [d, E] (dtype); w [B*N, E] and hbar [B*N, d] fp32 exactly as
+ *         lory_route wrote them; dw [B*N, E] fp32 (from lory_merged_ffn_bwd)
+ * in/out: dX [B, L, d] (dtype): the FFN path's input gradient, to which the
+ *         router path is added in place (bf16: one more rounding per element)
+ * out:    dR [d, E] fp32, overwritten, or added to when accumulate_dR = 1
+ * Sums run in a fixed order (bit-reproducible).  Needs no workspace.
+ * lory_route + lory_merged_ffn_fwd, then lory_merged_ffn_bwd + this call, are
+ * the whole layer of Algorithm 1 and its gradient.
+ */
+int lory_route_bwd(const lory_shape *shape, const void *R, const float *w, const float *hbar,
+                   const float *dw, void *dX, float *dR, int accumulate_dR, void *stream);
 
 /*
  * Merged FFN forward (Eq. 1 / Eq. 2 with SwiGLU experts):

@@ -26,7 +26,7 @@ LORY_PASS_FWD, LORY_PASS_BWD = 0, 1
 
 EXPORTS = ("lory_status_string", "lory_version", "lory_set_slab_budget", "lory_profile_enable",
            "lory_profile_read", "lory_merged_save_bytes", "lory_workspace_bytes", "lory_route",
-           "lory_merged_ffn_fwd", "lory_merged_ffn_bwd")
+           "lory_route_bwd", "lory_merged_ffn_fwd", "lory_merged_ffn_bwd")
 
 
 class LoryShape(ctypes.Structure):
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.lory_workspace_bytes.restype = ci
         L.lory_route.argtypes = [sp, vp, vp, vp, vp, vp]
         L.lory_route.restype = ci
+        L.lory_route_bwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, ci, vp]
+        L.lory_route_bwd.restype = ci
         L.lory_merged_save_bytes.argtypes = [sp, ctypes.POINTER(sz)]
         L.lory_merged_save_bytes.restype = ci
         L.lory_merged_ffn_fwd.argtypes = [sp] + [vp] * 10 + [sz, vp]
@@ -183,6 +185,30 @@ def lory_route(X: torch.Tensor, R: torch.Tensor, T: int, w: Optional[torch.Tenso
     _check(lib().lory_route(ctypes.byref(shape), _ptr(X), _ptr(R), _ptr(w), _ptr(hbar), _stream()),
            "lory_route")
     return w
+
+
+def lory_route_bwd(R: torch.Tensor, w: torch.Tensor, hbar: torch.Tensor, dw: torch.Tensor,
+                   dX: torch.Tensor, T: int, dR: Optional[torch.Tensor] = None, accumulate_dR: bool = False,
+                   d_ff: int = 64) -> torch.Tensor:
+    """Adds the router path to dX [B,L,d] in place and returns dR [d,E] fp32."""
+    B, L, d = dX.shape
+    E = R.shape[1]
+    if R.shape[0] != d or R.dtype != dX.dtype:
+        raise ValueError("R must be [d, E] with the dtype of dX")
+    S = B * (L // max(T, 1))
+    for name, t, shp in (("w", w, (S, E)), ("hbar", hbar, (S, d)), ("dw", dw, (S, E))):
+        if t.dtype != torch.float32 or tuple(t.shape) != shp:
+            raise ValueError(f"{name} must be fp32 {list(shp)}")
+    shape = _shape_from(dX, T, d_ff, E)
+    if dR is None:
+        if accumulate_dR:
+            raise ValueError("accumulate_dR needs a dR tensor")
+        dR = torch.empty((d, E), dtype=torch.float32, device=dX.device)
+    if dR.dtype != torch.float32 or tuple(dR.shape) != (d, E):
+        raise ValueError("dR must be fp32 [d, E]")
+    _check(lib().lory_route_bwd(ctypes.byref(shape), _ptr(R), _ptr(w), _ptr(hbar), _ptr(dw), _ptr(dX),
+                                _ptr(dR), int(bool(accumulate_dR)), _stream()), "lory_route_bwd")
+    return dR
 
 
 def lory_merged_ffn_fwd(X: torch.Tensor, w: torch.Tensor, Wg: torch.Tensor, Wu: torch.Tensor,

@@ -93,6 +93,26 @@ int lory_route(const lory_shape *shape, const void *X, const void *R, float *w, 
     return lory::route_launch(m, X, R, w, hbar_opt, nullptr, (hipStream_t)stream);
 }
 
+int lory_route_bwd(const lory_shape *shape, const void *R, const float *w, const float *hbar,
+                   const float *dw, void *dX, float *dR, int accumulate_dR, void *stream)
+{
+    const int rc = check_shape(shape);
+    if (rc != LORY_OK) return rc;
+    if (!R || !w || !hbar || !dw || !dX || !dR) return LORY_ERR_NULL;
+    if (accumulate_dR != 0 && accumulate_dR != 1) return LORY_ERR_SHAPE;
+    if (!aligned16(R) || !aligned16(w) || !aligned16(hbar) || !aligned16(dw) || !aligned16(dX) ||
+        !aligned16(dR))
+        return LORY_ERR_ALIGN;
+    const Dims m = lory::make_dims(*shape);
+    const double esz = (m.dtype == LORY_F32) ? 4.0 : 2.0;
+    // every segment but the last of each sequence has its rows of dX read and written
+    const double rows = (double)m.B * (m.N - 1) * m.T;
+    lory::prof::Range r((hipStream_t)stream, lory::prof::kRouteBwd,
+                        4.0 * m.S * m.d * m.E + rows * m.d,
+                        2.0 * esz * rows * m.d + 4.0 * ((double)m.S * m.d + (double)m.d * m.E));
+    return lory::route_bwd_launch(m, R, w, hbar, dw, dX, dR, accumulate_dR, (hipStream_t)stream);
+}
+
 int lory_merged_ffn_fwd(const lory_shape *shape, const void *X, const float *w, const void *Wg,
                         const void *Wu, const void *Wd, void *Y, void *G_save, void *U_save,
                         void *Wbar_save, void *workspace, size_t workspace_bytes, void *stream)

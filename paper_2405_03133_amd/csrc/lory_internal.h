@@ -43,7 +43,7 @@ inline int launch_status()
 // ---- optional event timing per kernel class (profile.hip)
 namespace prof {
 enum Class { kRoute = 0, kMerge, kGemmGU, kSwigluFwd, kGemmDown, kGemmDA, kSwigluBwd, kGemmDX, kGemmDWGU, kGemmDWD, kScatter,
-             kDwReduce, kNumClasses };
+             kDwReduce, kRouteBwd, kNumClasses };
 bool enabled();
 int set_enabled(int on);
 int read(lory_kernel_stat *out, int max_out, int *n_out);
@@ -64,6 +64,10 @@ private:
 int route_launch(const Dims &m, const void *X, const void *R, float *w, float *hbar,
                  float *hbar_scratch, hipStream_t st);
 size_t route_scratch_bytes(const Dims &m);
+
+// ---- routing backward (route_bwd.hip)
+int route_bwd_launch(const Dims &m, const void *R, const float *w, const float *hbar, const float *dw,
+                     void *dX, float *dR, int accumulate, hipStream_t st);
 
 // ---- fp32 path (ffn_f32.hip)
 size_t f32_workspace_bytes(const Dims &m, int pass);

@@ -65,6 +65,22 @@ def test_bad_dtype_and_nulls():
     assert L.lory_route(ctypes.byref(shape(L=500)), FAKE, FAKE, FAKE, None, None) == lb.LORY_ERR_SHAPE
 
 
+def test_route_bwd_validation():
+    L = lb.lib()
+    s = shape()
+    sp = ctypes.byref(s)
+    F = FAKE
+    for i in range(6):
+        args = [F] * 6
+        args[i] = None
+        assert L.lory_route_bwd(sp, *args, 0, None) == lb.LORY_ERR_NULL
+        args[i] = F + 4
+        assert L.lory_route_bwd(sp, *args, 0, None) == lb.LORY_ERR_ALIGN
+    assert L.lory_route_bwd(sp, F, F, F, F, F, F, 2, None) == lb.LORY_ERR_SHAPE
+    assert L.lory_route_bwd(ctypes.byref(shape(L=500)), F, F, F, F, F, F, 0, None) == lb.LORY_ERR_SHAPE
+    assert L.lory_route_bwd(None, F, F, F, F, F, F, 0, None) == lb.LORY_ERR_NULL
+
+
 @pytest.mark.parametrize("dtype", [lb.LORY_F32, lb.LORY_BF16])
 def test_workspace_query_and_ffn_validation(dtype):
     L = lb.lib()

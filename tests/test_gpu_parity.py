@@ -245,3 +245,78 @@ def test_merged_save_unsupported_shapes_are_rejected():
     assert lb.lory_merged_save_bytes(shape) == 0
     shape32 = lb.make_shape(2, 512, 128, 64, 256, 4, torch.float32)
     assert lb.lory_merged_save_bytes(shape32) == 0
+
+
+# ------------------------------------------------------------------ router backward
+
+ROUTE_BWD_CASES = [
+    CONFIGS["C1"],
+    LoryConfig("f32_ragged_dims", B=3, L=60, T=20, d=50, d_ff=70, E=5, dtype="f32", seed=21),
+    LoryConfig("f32_single_segment", B=2, L=48, T=48, d=32, d_ff=96, E=3, dtype="f32", seed=22),
+    LoryConfig("f32_max_experts", B=1, L=32, T=8, d=16, d_ff=24, E=64, dtype="f32", seed=24),
+    LoryConfig("f32_one_token_segments", B=2, L=6, T=1, d=12, d_ff=20, E=4, dtype="f32", seed=25),
+    LoryConfig("f32_many_segments", B=2, L=640, T=4, d=40, d_ff=8, E=6, dtype="f32", seed=26),
+    LoryConfig("bf16_route_bwd", B=2, L=512, T=64, d=192, d_ff=64, E=8, dtype="bf16", seed=41),
+    LoryConfig("bf16_route_bwd_E33", B=3, L=384, T=128, d=320, d_ff=64, E=33, dtype="bf16", seed=42),
+]
+
+
+@pytest.mark.parametrize("cfg", ROUTE_BWD_CASES, ids=lambda c: c.name)
+def test_route_bwd_matches_oracle(cfg):
+    """lory_route_bwd against the oracle's router backward, fed the same dw.
+
+    The routing here is peaked (structured inputs) so that the softmax Jacobian is far from
+    degenerate; dw is a seeded N(0,1) tensor, not the FFN's, so that the router path is not small.
+    """
+    print(f"[gpu] route_bwd {cfg}", flush=True)
+    t = make_inputs(cfg, structured=True)
+    rng = np.random.Generator(np.random.Philox(cfg.seed + 900))
+    dw = rng.standard_normal((cfg.S, cfg.E)).astype(np.float32)
+    X, R = to_dev(t["X"], cfg), to_dev(t["R"], cfg)
+    hbar = torch.empty((cfg.S, cfg.d), dtype=torch.float32, device="cuda")
+    w = lb.lory_route(X, R, cfg.T, hbar=hbar, d_ff=cfg.d_ff)
+    dw_d = torch.from_numpy(dw).cuda()
+    # (1) router path alone: added to zeros
+    dX0 = torch.zeros_like(X)
+    dR = lb.lory_route_bwd(R, w, hbar, dw_d, dX0, cfg.T, d_ff=cfg.d_ff)
+    # (2) added in place to an existing gradient, dR accumulated on top of the first result
+    base = to_dev(t["dY"], cfg)
+    dX1 = base.clone()
+    dR2 = dR.clone()
+    lb.lory_route_bwd(R, w, hbar, dw_d, dX1, cfg.T, dR=dR2, accumulate_dR=True, d_ff=cfg.d_ff)
+    torch.cuda.synchronize()
+    ref = orc.route_bwd(t["X"], t["R"], dw.astype(np.float64), cfg.T)
+    tol = 1e-4 if cfg.dtype == "f32" else TOL["bf16"]   # fp32: forward softmax and means are fp32
+    if cfg.N == 1:
+        assert not ref["dX_add"].any() and not ref["dR"].any()
+        assert not host(dX0).any() and not host(dR).any()
+        assert torch.equal(dX1, base)
+        return
+    got = {"dX_add": host(dX0), "dR": host(dR)}
+    compare(cfg, got, ref, ("dX_add", "dR"), tol)
+    total = host(base) + ref["dX_add"].reshape(host(base).shape)
+    compare(cfg, {"dX_total": host(dX1)}, {"dX_total": total}, ("dX_total",), tol)
+    np.testing.assert_array_equal(host(dR2), 2.0 * host(dR))
+    # rows of the last segment of every sequence get nothing from the router path
+    last = host(dX0).reshape(cfg.B, cfg.N, cfg.T, cfg.d)[:, -1]
+    assert not last.any()
+
+
+def test_whole_layer_gradient_fp32():
+    """route -> fwd -> bwd -> route_bwd on the GPU against the oracle's whole-layer gradient."""
+    cfg = CONFIGS["C1"]
+    t = make_inputs(cfg, structured=True)
+    X, R = to_dev(t["X"], cfg), to_dev(t["R"], cfg)
+    Wg, Wu, Wd = (to_dev(t[k], cfg) for k in ("Wg", "Wu", "Wd"))
+    dY = to_dev(t["dY"], cfg)
+    hbar = torch.empty((cfg.S, cfg.d), dtype=torch.float32, device="cuda")
+    w = lb.lory_route(X, R, cfg.T, hbar=hbar, d_ff=cfg.d_ff)
+    lb.lory_merged_ffn_fwd(X, w, Wg, Wu, Wd, cfg.T)
+    dX, dWg, dWu, dWd, dw = lb.lory_merged_ffn_bwd(X, w, Wg, Wu, Wd, dY, cfg.T)
+    dR = lb.lory_route_bwd(R, w, hbar, dw, dX, cfg.T, d_ff=cfg.d_ff)
+    torch.cuda.synchronize()
+    ref = orc.layer_bwd(t["X"], t["R"], t["Wg"], t["Wu"], t["Wd"], t["dY"], cfg.T)
+    got = {"dX": host(dX), "dR": host(dR), "dWg": host(dWg), "dWu": host(dWu), "dWd": host(dWd)}
+    compare(cfg, got, ref, ("dX", "dWg", "dWu", "dWd"), 2e-5)
+    compare(cfg, got, ref, ("dR",), 1e-3)   # dR inherits the fp32 rounding of dw through a cancelling sum
+    assert np.linalg.norm(ref["dR"]) > 0
