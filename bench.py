@@ -49,6 +49,9 @@ def parse_args():
                     help="do not hand the forward's merged parameters to the backward (it re-merges)")
     ap.add_argument("--slab-mb", type=int, default=0)
     ap.add_argument("--verbose", action="store_true")
+    ap.add_argument("--mode", default="train", choices=["train", "infer"],
+                    help="train: the headline step (default).  infer: prompt-only routing, one merge per "
+                         "sequence from a prompt of L tokens, then decode steps of one token per sequence")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic) so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -80,12 +83,78 @@ def cpu_baseline(cfg, verbose=False):
                       f"(route+fwd+bwd+route_bwd, fp64, {dt:.1f} s)"}
 
 
+def bench_infer(args):
+    """Prompt-only routing at inference: lory_prompt_merge once, then lory_dense_ffn_fwd decode steps."""
+    import torch
+    from paper_2405_03133_amd import binding as lb
+    from paper_2405_03133_amd.inputs import CONFIGS
+
+    cfg = CONFIGS[args.config]
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    dt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed)
+
+    def normal(shape, sigma):
+        return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * sigma).to(dt)
+
+    Xp = normal((cfg.B, cfg.L, cfg.d), 1.0)
+    R = normal((cfg.d, cfg.E), 0.02)
+    Wg = normal((cfg.E, cfg.d, cfg.d_ff), 0.02)
+    Wu = normal((cfg.E, cfg.d, cfg.d_ff), 0.02)
+    Wd = normal((cfg.E, cfg.d_ff, cfg.d), 0.02)
+    x1 = normal((cfg.B, 1, cfg.d), 1.0)
+    w, Wbar = lb.lory_prompt_merge(Xp, R, Wg, Wu, Wd)
+    y1 = torch.empty_like(x1)
+    ws = lb.alloc_workspace(lb.make_shape(cfg.B, 1, 1, cfg.d, cfg.d_ff, 1, dt), lb.LORY_PASS_DENSE)
+
+    def timed(fn, n):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    t_merge = timed(lambda: lb.lory_prompt_merge(Xp, R, Wg, Wu, Wd, w=w, Wbar=Wbar), args.steps)
+    n_dec = max(args.steps * 20, 50)
+    t_dec = timed(lambda: lb.lory_dense_ffn_fwd(x1, Wbar, cfg.d_ff, Y=y1, workspace=ws), n_dec)
+    lb.lory_profile_enable(True)
+    for _ in range(n_dec):
+        lb.lory_dense_ffn_fwd(x1, Wbar, cfg.d_ff, Y=y1, workspace=ws)
+    torch.cuda.synchronize()
+    stats = {s["name"]: s for s in lb.lory_profile_read()}
+    lb.lory_profile_enable(False)
+    sk = stats["dense_skinny"]
+    gbs = sk["bytes"] / (sk["ms"] * 1e-3) / 1e9
+    out = {
+        "metric": "decode tokens/sec/GPU with prompt-only routing (one layer's merged FFN)",
+        "value": cfg.B / t_dec, "unit": "tokens/s", "n_gpus": 1, "steps": n_dec, "warmup": args.warmup,
+        "ms_per_step": 1e3 * t_dec, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name} experts: B={cfg.B} sequences, prompt of {cfg.L} tokens routed once, "
+                               f"then 1 token per sequence and step; d={cfg.d} d_ff={cfg.d_ff} E={cfg.E}"},
+        "prompt_merge_ms": 1e3 * t_merge,
+        "roofline": {"kernel": "dense_skinny", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "avg_launch_us": 1e3 * sk["ms"] / sk["launches"],
+                     "traffic": None},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives are part of it)",
               file=sys.stderr)
         sys.exit(2)
+    if args.mode == "infer":
+        bench_infer(args)
+        return
 
     import torch
     from paper_2405_03133_amd import binding as lb

@@ -51,7 +51,7 @@ typedef enum {
 
 typedef enum { LORY_F32 = 0, LORY_BF16 = 1 } lory_dtype;
 
-typedef enum { LORY_PASS_FWD = 0, LORY_PASS_BWD = 1 } lory_pass;
+typedef enum { LORY_PASS_FWD = 0, LORY_PASS_BWD = 1, LORY_PASS_DENSE = 2 } lory_pass;
 
 /* Problem statement of Algorithm 1: x is B x L x d, E experts, segment
  * length T; d_ff is the FFN width (the paper's d'). */
@@ -100,8 +100,9 @@ int lory_profile_enable(int on);
 int lory_profile_read(lory_kernel_stat *out, int max_out, int *n_out);
 
 /*
- * Bytes of device workspace that lory_merged_ffn_fwd (pass = LORY_PASS_FWD)
- * or lory_merged_ffn_bwd (pass = LORY_PASS_BWD) needs for this shape.  The
+ * Bytes of device workspace that lory_merged_ffn_fwd (pass = LORY_PASS_FWD),
+ * lory_merged_ffn_bwd (pass = LORY_PASS_BWD) or lory_dense_ffn_fwd (pass =
+ * LORY_PASS_DENSE, shape as that call takes it) needs for this shape.  The
  * workspace holds only transient data (merged-weight slabs, per-segment
  * weight-gradient slabs, activations between the two projections, partial
  * router-weight gradients); its contents are undefined before and after a
@@ -155,6 +156,42 @@ int lory_route(const lory_shape *shape, const void *X, const void *R,
  */
 int lory_route_bwd(const lory_shape *shape, const void *R, const float *w, const float *hbar,
                    const float *dw, void *dX, float *dR, int accumulate_dR, void *stream);
+
+/*
+ * Prompt-only routing at inference (Section 3.1, "Prompt-only routing during
+ * inference"; Appendix G.1): one routing decision per sequence and layer from
+ * the mean hidden state of the whole prompt, and the merged FFN it selects,
+ * materialised once and then used like a dense FFN for the whole generation.
+ *   w[b,:]   = softmax(mean over the L prompt tokens of X_prompt[b] . R)
+ *   Wx_bar_b = sum_e w[b,e] Wx[e]      x in {gate, up, down}
+ * shape: L = prompt length (any length > 0, the same for all B sequences) and
+ *        T = L (one segment per sequence; anything else is LORY_ERR_SHAPE);
+ *        LORY_BF16 needs d % 64 == 0 and d_ff % 64 == 0 only.
+ * in:  X_prompt [B, L, d], R [d, E], Wg, Wu [E, d, d_ff], Wd [E, d_ff, d] (dtype)
+ * out: w [B, E] fp32; Wbar: 3 * B * d * d_ff elements of dtype, laid out
+ *      [Wg_bar | Wu_bar | Wd_bar], each [B, rows, cols] like one expert matrix
+ *      (the layout of Wbar_save).  Needs no workspace.
+ * Per-segment routing at inference, the other mode the paper evaluates, is
+ * lory_route + lory_merged_ffn_fwd as in training.
+ */
+int lory_prompt_merge(const lory_shape *shape, const void *X_prompt, const void *R,
+                      const void *Wg, const void *Wu, const void *Wd,
+                      float *w, void *Wbar, void *stream);
+
+/*
+ * Dense SwiGLU FFN of every sequence with its own merged parameters, i.e. the
+ * generation phase after lory_prompt_merge (or after a lory_merged_ffn_fwd
+ * with T = L that filled Wbar_save):
+ *   Y[b] = (G * sigmoid(G) (.) U) Wd_bar_b,  G = X[b] Wg_bar_b, U = X[b] Wu_bar_b
+ * shape: L = tokens per sequence in this call (1 for a decode step), T = L.
+ * in:  X [B, L, d] (dtype); Wbar as lory_prompt_merge wrote it
+ * out: Y [B, L, d] (dtype)
+ * LORY_BF16 with L % 64 == 0 runs on the batched matrix-core GEMMs; every other
+ * case runs HBM-bound kernels that read each weight once per 8 tokens.
+ * workspace: lory_workspace_bytes(shape, LORY_PASS_DENSE).
+ */
+int lory_dense_ffn_fwd(const lory_shape *shape, const void *X, const void *Wbar, void *Y,
+                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Merged FFN forward (Eq. 1 / Eq. 2 with SwiGLU experts):

@@ -22,11 +22,12 @@ LIB_PATH = os.path.join(_HERE, "liblory.so")
 LORY_OK = 0
 LORY_ERR_NULL, LORY_ERR_SHAPE, LORY_ERR_DTYPE, LORY_ERR_ALIGN, LORY_ERR_WORKSPACE, LORY_ERR_DEVICE = range(1, 7)
 LORY_F32, LORY_BF16 = 0, 1
-LORY_PASS_FWD, LORY_PASS_BWD = 0, 1
+LORY_PASS_FWD, LORY_PASS_BWD, LORY_PASS_DENSE = 0, 1, 2
 
 EXPORTS = ("lory_status_string", "lory_version", "lory_set_slab_budget", "lory_profile_enable",
            "lory_profile_read", "lory_merged_save_bytes", "lory_workspace_bytes", "lory_route",
-           "lory_route_bwd", "lory_merged_ffn_fwd", "lory_merged_ffn_bwd")
+           "lory_route_bwd", "lory_merged_ffn_fwd", "lory_merged_ffn_bwd", "lory_prompt_merge",
+           "lory_dense_ffn_fwd")
 
 
 class LoryShape(ctypes.Structure):
@@ -74,6 +75,10 @@ def lib() -> ctypes.CDLL:
         L.lory_route.restype = ci
         L.lory_route_bwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, ci, vp]
         L.lory_route_bwd.restype = ci
+        L.lory_prompt_merge.argtypes = [sp] + [vp] * 8
+        L.lory_prompt_merge.restype = ci
+        L.lory_dense_ffn_fwd.argtypes = [sp, vp, vp, vp, vp, sz, vp]
+        L.lory_dense_ffn_fwd.restype = ci
         L.lory_merged_save_bytes.argtypes = [sp, ctypes.POINTER(sz)]
         L.lory_merged_save_bytes.restype = ci
         L.lory_merged_ffn_fwd.argtypes = [sp] + [vp] * 10 + [sz, vp]
@@ -209,6 +214,47 @@ def lory_route_bwd(R: torch.Tensor, w: torch.Tensor, hbar: torch.Tensor, dw: tor
     _check(lib().lory_route_bwd(ctypes.byref(shape), _ptr(R), _ptr(w), _ptr(hbar), _ptr(dw), _ptr(dX),
                                 _ptr(dR), int(bool(accumulate_dR)), _stream()), "lory_route_bwd")
     return dR
+
+
+def lory_prompt_merge(X_prompt: torch.Tensor, R: torch.Tensor, Wg: torch.Tensor, Wu: torch.Tensor,
+                      Wd: torch.Tensor, w: Optional[torch.Tensor] = None,
+                      Wbar: Optional[torch.Tensor] = None):
+    """Prompt-only routing: (w [B,E] fp32, Wbar [3, B, d*d_ff] of X's dtype) from the whole prompt."""
+    B, L, d = X_prompt.shape
+    E, _, d_ff = Wg.shape
+    if tuple(Wu.shape) != (E, d, d_ff) or tuple(Wd.shape) != (E, d_ff, d) or tuple(R.shape) != (d, E):
+        raise ValueError("R / expert stack shapes do not match")
+    for t in (R, Wg, Wu, Wd):
+        if t.dtype != X_prompt.dtype:
+            raise TypeError("R and the expert stacks must have the dtype of X_prompt")
+    shape = make_shape(B, L, L, d, d_ff, E, X_prompt.dtype)
+    if w is None:
+        w = torch.empty((B, E), dtype=torch.float32, device=X_prompt.device)
+    if Wbar is None:
+        Wbar = torch.empty((3, B, d * d_ff), dtype=X_prompt.dtype, device=X_prompt.device)
+    if w.dtype != torch.float32 or tuple(w.shape) != (B, E):
+        raise ValueError("w must be fp32 [B, E]")
+    if Wbar.dtype != X_prompt.dtype or Wbar.numel() != 3 * B * d * d_ff:
+        raise ValueError("Wbar must hold 3*B*d*d_ff elements of X's dtype")
+    _check(lib().lory_prompt_merge(ctypes.byref(shape), _ptr(X_prompt), _ptr(R), _ptr(Wg), _ptr(Wu), _ptr(Wd),
+                                   _ptr(w), _ptr(Wbar), _stream()), "lory_prompt_merge")
+    return w, Wbar
+
+
+def lory_dense_ffn_fwd(X: torch.Tensor, Wbar: torch.Tensor, d_ff: int, Y: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y [B,L,d] = dense SwiGLU FFN of every sequence with its merged parameters Wbar."""
+    B, L, d = X.shape
+    if Wbar.dtype != X.dtype or Wbar.numel() != 3 * B * d * d_ff:
+        raise ValueError("Wbar must hold 3*B*d*d_ff elements of X's dtype")
+    shape = make_shape(B, L, L, d, d_ff, 1, X.dtype)
+    if Y is None:
+        Y = torch.empty_like(X)
+    if workspace is None:
+        workspace = alloc_workspace(shape, LORY_PASS_DENSE, X.device)
+    _check(lib().lory_dense_ffn_fwd(ctypes.byref(shape), _ptr(X), _ptr(Wbar), _ptr(Y), _ptr(workspace),
+                                    workspace.numel(), _stream()), "lory_dense_ffn_fwd")
+    return Y
 
 
 def lory_merged_ffn_fwd(X: torch.Tensor, w: torch.Tensor, Wg: torch.Tensor, Wu: torch.Tensor,

@@ -233,6 +233,58 @@ int bf16_ffn_fwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
     return LORY_OK;
 }
 
+// Merged parameters of all m.S segments, materialised as [Wg_bar | Wu_bar | Wd_bar], each
+// [S][rows][cols] (the layout of Wbar_save).
+int bf16_merge_all(const Dims &m, const float *w, const void *Wgv, const void *Wuv, const void *Wdv,
+                   void *Wbarv, hipStream_t st)
+{
+    const Plan pl = make_plan(m);
+    const bf *stacks[3] = {(const bf *)Wgv, (const bf *)Wuv, (const bf *)Wdv};
+    const Rect rcs[3] = {rect(m.D, m.dff, 0, m.d, 0, m.dff), rect(m.D, m.dff, 0, m.d, 0, m.dff),
+                         rect(m.D, m.d, 0, m.dff, 0, m.d)};
+    bf *out = (bf *)Wbarv;
+    for (int s0 = 0; s0 < m.S; s0 += pl.Sc) {
+        const int S = (m.S - s0 < pl.Sc) ? (m.S - s0) : pl.Sc;
+        for (int x = 0; x < 3; ++x)
+            LORY_TRY(merge(st, w + (size_t)s0 * m.E, S, m.E, stacks[x], rcs[x],
+                           out + ((size_t)x * m.S + s0) * m.D));
+    }
+    return LORY_OK;
+}
+
+size_t bf16_dense_workspace_bytes(const Dims &m) { return align_up((size_t)m.tokens * m.dff * 2, 256); }
+
+// Dense SwiGLU FFN of every sequence with its own materialised merged parameters
+// (m.T == m.L: one parameter set per sequence, T a multiple of 64).
+int bf16_dense_ffn_fwd(const Dims &m, const void *Xv, const void *Wbarv, void *Yv, void *ws, hipStream_t st)
+{
+    const bf *X = (const bf *)Xv, *Wbar = (const bf *)Wbarv;
+    bf *Y = (bf *)Yv, *Act = (bf *)ws;
+    const long TD = (long)m.T * m.d, TF = (long)m.T * m.dff;
+    {
+        Params p = {};
+        p.A[0] = X; p.a_batch[0] = TD; p.lda[0] = m.d;
+        p.B[0] = Wbar; p.b_batch[0] = m.D; p.ldb[0] = m.dff;
+        p.B[1] = Wbar + (size_t)m.S * m.D; p.b_batch[1] = m.D; p.ldb[1] = m.dff;
+        p.M = m.T; p.N = m.dff; p.K = m.d; p.batches = m.S;
+        EpiGU epi = {nullptr, nullptr, Act, m.T, m.dff, 0};
+        prof::Range r(st, prof::kGemmGU, gemm_flops(p, 2, 1),
+                      2.0 * ((double)m.S * TD + 2.0 * m.S * m.D + (double)m.S * TF));
+        LORY_TRY(k::launch_gu(st, p, epi));
+    }
+    {
+        Params p = {};
+        p.A[0] = Act; p.a_batch[0] = TF; p.lda[0] = m.dff;
+        p.B[0] = Wbar + (size_t)2 * m.S * m.D; p.b_batch[0] = m.D; p.ldb[0] = m.d;
+        p.M = m.T; p.N = m.d; p.K = m.dff; p.batches = m.S;
+        EpiStore epi = {Y, TD, m.d};
+        prof::Range r(st, prof::kGemmDown, gemm_flops(p, 1, 1),
+                      2.0 * ((double)m.S * TF + (double)m.S * m.D + (double)m.S * TD));
+        LORY_TRY(k::launch_down(st, p, epi));
+    }
+    return LORY_OK;
+}
+
 int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv, const void *Wuv,
                  const void *Wdv, const void *dYv, const void *Gv, const void *Uv, const void *Wbarv,
                  void *dXv, void *dWg, void *dWu, void *dWd, int grad_dtype, int accumulate, float *dw,

@@ -223,6 +223,19 @@ int f32_ffn_fwd(const Dims &m, const float *X, const float *w, const float *Wg, 
     return launch_status();
 }
 
+// Merged parameters of all m.S segments as [Wg_bar | Wu_bar | Wd_bar], each [S][rows][cols].
+int f32_merge_all(const Dims &m, const float *w, const float *Wg, const float *Wu, const float *Wd,
+                  float *Wbar, hipStream_t st)
+{
+    const float *stacks[3] = {Wg, Wu, Wd};
+    for (int x = 0; x < 3; ++x)
+        for (int s0 = 0; s0 < m.S; s0 += 32768) {  // grid.y limit
+            const int sc = (m.S - s0 < 32768) ? (m.S - s0) : 32768;
+            merge(st, w + (size_t)s0 * m.E, stacks[x], Wbar + ((size_t)x * m.S + s0) * m.D, m.D, m.E, sc);
+        }
+    return launch_status();
+}
+
 int f32_ffn_bwd(const Dims &m, const float *X, const float *w, const float *Wg, const float *Wu,
                 const float *Wd, const float *dY, const float *G_save, const float *U_save,
                 float *dX, float *dWg, float *dWu, float *dWd, int accumulate, float *dw, void *ws,

@@ -1,0 +1,307 @@
+// Dense SwiGLU FFN with per-sequence merged parameters: the generation phase of
+// prompt-only routing (paper Section 3.1, "Prompt-only routing during
+// inference"; Appendix G.1).  After one routing decision per layer the merged
+// FFN of a sequence is an ordinary dense FFN,
+//   Y_b = (silu(X_b Wg_bar_b) (.) X_b Wu_bar_b) Wd_bar_b .
+// Long token blocks (bf16, a multiple of 64 tokens per sequence) go through the
+// batched MFMA GEMMs.  Everything else (decode steps of one or a few tokens,
+// fp32, ragged token counts) goes through the "skinny" kernels below, which are
+// HBM-bound: every weight is read once per pass of up to 8 tokens.
+//
+// Skinny pass, per matrix product out[t][n] = sum_k x[t][k] W[k][n], W row-major:
+//   grid (column blocks, K splits, sequences); a wavefront covers 64 * VEC
+//   consecutive columns with one 16-byte load per lane and row; the 4 wavefronts
+//   of a workgroup take interleaved rows of its K slice; x is staged in LDS as
+//   fp32; partial sums go to [K split][sequence][matrix][token][n] in the
+//   workspace and are added in split order by the finishing kernels (SwiGLU for
+//   gate/up, store for down) => bit-reproducible.
+#include "lory_internal.h"
+
+#include <hip/hip_bf16.h>
+
+namespace lory {
+
+namespace {
+
+constexpr int kSkThreads = 256;
+constexpr int kMaxTok = 8;        // tokens per skinny pass
+constexpr int kMaxSlice = 512;    // rows of W per workgroup (x slice in LDS: 8 * 512 floats)
+
+template <typename T> struct Ld;
+template <> struct Ld<float> {
+    static constexpr int vec = 4;
+    __device__ static void load(const float *p, float (&v)[4])
+    {
+        const float4 q = *reinterpret_cast<const float4 *>(p);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    }
+    __device__ static float one(const float *p) { return *p; }
+    __device__ static void store(float *p, float v) { *p = v; }
+};
+template <> struct Ld<__hip_bfloat16> {
+    static constexpr int vec = 8;
+    __device__ static void load(const __hip_bfloat16 *p, float (&v)[8])
+    {
+        const uint4 q = *reinterpret_cast<const uint4 *>(p);
+        const uint32_t r[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(r[i] << 16);
+            v[2 * i + 1] = __uint_as_float(r[i] & 0xffff0000u);
+        }
+    }
+    __device__ static float one(const __hip_bfloat16 *p)
+    {
+        return __uint_as_float(((uint32_t) * reinterpret_cast<const uint16_t *>(p)) << 16);
+    }
+    __device__ static void store(__hip_bfloat16 *p, float f)
+    {
+        const uint32_t u = __float_as_uint(f);
+        uint16_t h;
+        if ((u & 0x7fffffffu) > 0x7f800000u)
+            h = (uint16_t)((u >> 16) | 0x40u);
+        else
+            h = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+        *reinterpret_cast<uint16_t *>(p) = h;
+    }
+};
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(__hip_bfloat16 v) { return Ld<__hip_bfloat16>::one(&v); }
+
+// TW: storage type of the weights.  TX: type of x (TW for the layer input, float for the
+// activation between the two phases).  MT tokens, NMAT matrices sharing x (2 = gate and up),
+// VEC columns per lane (Ld<TW>::vec, or 1 when N is not a multiple of it).
+//   x:    [B][x_rows][K]   (token t of sequence b at x + (b * x_rows + t) * K)
+//   W0/1: [B][K][N]
+//   part: [ksplit][B][NMAT][MT][N] fp32
+template <typename TW, typename TX, int MT, int NMAT, int VEC>
+__global__ __launch_bounds__(kSkThreads) void skinny_kernel(const TX *__restrict__ x, long x_rows,
+                                                            const TW *__restrict__ W0,
+                                                            const TW *__restrict__ W1, float *__restrict__ part,
+                                                            int K, int N, int slice)
+{
+    __shared__ float xs[kMaxTok * kMaxSlice];
+    __shared__ float red[3][64 * VEC];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.z, B = gridDim.z;
+    const int k0 = blockIdx.y * slice;
+    const int k1 = (k0 + slice < K) ? (k0 + slice) : K;
+    const int c = (blockIdx.x * 64 + lane) * VEC;
+
+    for (int i = tid; i < MT * (k1 - k0); i += kSkThreads) {
+        const int t = i / (k1 - k0), k = i - t * (k1 - k0);
+        xs[t * kMaxSlice + k] = to_f32(x[((size_t)b * x_rows + t) * K + k0 + k]);
+    }
+    __syncthreads();
+
+    float acc[NMAT][MT][VEC];
+#pragma unroll
+    for (int a = 0; a < NMAT; ++a)
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[a][t][i] = 0.f;
+
+    if (c < N) {
+        const TW *Wb[2] = {W0 + (size_t)b * K * N + c, NMAT == 2 ? W1 + (size_t)b * K * N + c : nullptr};
+#pragma unroll 4
+        for (int k = k0 + wave; k < k1; k += 4) {
+            float wv[NMAT][VEC];
+#pragma unroll
+            for (int a = 0; a < NMAT; ++a) {
+                if constexpr (VEC == 1)
+                    wv[a][0] = Ld<TW>::one(Wb[a] + (size_t)k * N);
+                else
+                    Ld<TW>::load(Wb[a] + (size_t)k * N, wv[a]);
+            }
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                const float xv = xs[t * kMaxSlice + (k - k0)];
+#pragma unroll
+                for (int a = 0; a < NMAT; ++a)
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc[a][t][i] = fmaf(xv, wv[a][i], acc[a][t][i]);
+            }
+        }
+    }
+
+    // the four wavefronts' sums, added in wavefront order by wavefront 0
+    float *dst = part + (((size_t)blockIdx.y * B + b) * NMAT) * MT * N;
+#pragma unroll
+    for (int a = 0; a < NMAT; ++a)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            if (wave > 0) {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) red[wave - 1][lane * VEC + i] = acc[a][t][i];
+            }
+            __syncthreads();
+            if (wave == 0 && c < N) {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    float v = acc[a][t][i];
+                    v += red[0][lane * VEC + i];
+                    v += red[1][lane * VEC + i];
+                    v += red[2][lane * VEC + i];
+                    dst[((size_t)a * MT + t) * N + c + i] = v;
+                }
+            }
+            __syncthreads();
+        }
+}
+
+// act[b][t][n] = silu(g) * u with g, u summed over the K splits.   part: [ks][B][2][mt][N]
+__global__ void skinny_finish_gu_kernel(const float *__restrict__ part, float *__restrict__ act, int ksplit,
+                                        int B, int mt, int N)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long total = (long)B * mt * N;
+    if (i >= total) return;
+    const int n = (int)(i % N);
+    const int t = (int)((i / N) % mt);
+    const int b = (int)(i / ((long)N * mt));
+    float g = 0.f, u = 0.f;
+    for (int ks = 0; ks < ksplit; ++ks) {
+        const float *p = part + (((size_t)ks * B + b) * 2) * mt * N;
+        g += p[(size_t)t * N + n];
+        u += p[((size_t)mt + t) * N + n];
+    }
+    act[i] = g / (1.0f + expf(-g)) * u;
+}
+
+// Y[b][t0 + t][j] = sum over the K splits.   part: [ks][B][1][mt][N]
+template <typename T>
+__global__ void skinny_finish_down_kernel(const float *__restrict__ part, T *__restrict__ Y, int ksplit, int B,
+                                          int mt, int N, long y_rows, int t0)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long total = (long)B * mt * N;
+    if (i >= total) return;
+    const int n = (int)(i % N);
+    const int t = (int)((i / N) % mt);
+    const int b = (int)(i / ((long)N * mt));
+    float y = 0.f;
+    for (int ks = 0; ks < ksplit; ++ks) y += part[(((size_t)ks * B + b) * mt + t) * N + n];
+    Ld<T>::store(Y + ((size_t)b * y_rows + t0 + t) * N + n, y);
+}
+
+// K splits: enough workgroups to fill the chip, slices of at most kMaxSlice rows.
+int choose_ksplit(int K, int N, int B, int vec)
+{
+    const int colblocks = (N + 64 * vec - 1) / (64 * vec);
+    int ks = (1024 + colblocks * B - 1) / (colblocks * B);
+    const int min_ks = (K + kMaxSlice - 1) / kMaxSlice;
+    if (ks < min_ks) ks = min_ks;
+    const int max_ks = (K + 15) / 16;  // at least 16 rows per slice
+    if (ks > max_ks) ks = max_ks;
+    if (ks < 1) ks = 1;
+    return ks;
+}
+
+struct SkinnyPlan {
+    int vec1, vec2;     // columns per lane in the two phases
+    int ks1, ks2;       // K splits
+    size_t part;        // floats of the partial-sum area
+    size_t act;         // floats of the activation area
+};
+
+template <typename T>
+SkinnyPlan skinny_plan(const Dims &m)
+{
+    SkinnyPlan p;
+    p.vec1 = (m.dff % Ld<T>::vec == 0) ? Ld<T>::vec : 1;
+    p.vec2 = (m.d % Ld<T>::vec == 0) ? Ld<T>::vec : 1;
+    p.ks1 = choose_ksplit(m.d, m.dff, m.B, p.vec1);
+    p.ks2 = choose_ksplit(m.dff, m.d, m.B, p.vec2);
+    const size_t p1 = (size_t)p.ks1 * m.B * 2 * kMaxTok * m.dff;
+    const size_t p2 = (size_t)p.ks2 * m.B * kMaxTok * m.d;
+    p.part = p1 > p2 ? p1 : p2;
+    p.act = (size_t)m.B * kMaxTok * m.dff;
+    return p;
+}
+
+template <typename TW, typename TX, int NMAT, int VEC>
+void launch_skinny(hipStream_t st, int mt, dim3 grid, const TX *x, long x_rows, const TW *W0, const TW *W1,
+                   float *part, int K, int N, int slice)
+{
+#define LORY_SK(M)                                                                                           \
+    hipLaunchKernelGGL((skinny_kernel<TW, TX, M, NMAT, VEC>), grid, dim3(kSkThreads), 0, st, x, x_rows, W0, \
+                       W1, part, K, N, slice)
+    switch (mt) {
+    case 1: LORY_SK(1); break;
+    case 2: LORY_SK(2); break;
+    case 3: LORY_SK(3); break;
+    case 4: LORY_SK(4); break;
+    case 5: LORY_SK(5); break;
+    case 6: LORY_SK(6); break;
+    case 7: LORY_SK(7); break;
+    default: LORY_SK(8); break;
+    }
+#undef LORY_SK
+}
+
+template <typename T>
+int skinny_ffn(const Dims &m, const T *X, const T *Wbar, T *Y, void *ws, hipStream_t st)
+{
+    const SkinnyPlan pl = skinny_plan<T>(m);
+    float *part = (float *)ws;
+    float *act = part + pl.part;
+    const T *Wg = Wbar, *Wu = Wbar + (size_t)m.B * m.D, *Wd = Wbar + (size_t)2 * m.B * m.D;
+    const int slice1 = (m.d + pl.ks1 - 1) / pl.ks1, slice2 = (m.dff + pl.ks2 - 1) / pl.ks2;
+    const int ks1 = (m.d + slice1 - 1) / slice1, ks2 = (m.dff + slice2 - 1) / slice2;
+    const double esz = sizeof(T);
+    for (int t0 = 0; t0 < m.L; t0 += kMaxTok) {
+        const int mt = (m.L - t0 < kMaxTok) ? (m.L - t0) : kMaxTok;
+        prof::Range r(st, prof::kDenseSkinny, 6.0 * m.B * mt * (double)m.D,
+                      esz * (3.0 * m.B * m.D + 2.0 * m.B * mt * m.d));
+        // phase 1: gate and up partial sums, then SwiGLU
+        {
+            const dim3 grid((m.dff + 64 * pl.vec1 - 1) / (64 * pl.vec1), ks1, m.B);
+            const T *x = X + (size_t)t0 * m.d;
+            if (pl.vec1 == 1)
+                launch_skinny<T, T, 2, 1>(st, mt, grid, x, m.L, Wg, Wu, part, m.d, m.dff, slice1);
+            else
+                launch_skinny<T, T, 2, Ld<T>::vec>(st, mt, grid, x, m.L, Wg, Wu, part, m.d, m.dff, slice1);
+            const long n = (long)m.B * mt * m.dff;
+            hipLaunchKernelGGL(skinny_finish_gu_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part,
+                               act, ks1, m.B, mt, m.dff);
+        }
+        // phase 2: down projection
+        {
+            const dim3 grid((m.d + 64 * pl.vec2 - 1) / (64 * pl.vec2), ks2, m.B);
+            if (pl.vec2 == 1)
+                launch_skinny<T, float, 1, 1>(st, mt, grid, act, mt, Wd, (const T *)nullptr, part, m.dff, m.d,
+                                              slice2);
+            else
+                launch_skinny<T, float, 1, Ld<T>::vec>(st, mt, grid, act, mt, Wd, (const T *)nullptr, part,
+                                                       m.dff, m.d, slice2);
+            const long n = (long)m.B * mt * m.d;
+            hipLaunchKernelGGL((skinny_finish_down_kernel<T>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                               st, part, Y, ks2, m.B, mt, m.d, (long)m.L, t0);
+        }
+        if (hipGetLastError() != hipSuccess) return LORY_ERR_DEVICE;
+    }
+    return LORY_OK;
+}
+
+bool gemm_path(const Dims &m) { return m.dtype == LORY_BF16 && m.L % 64 == 0; }
+
+}  // namespace
+
+size_t dense_workspace_bytes(const Dims &m)
+{
+    if (gemm_path(m)) return bf16_dense_workspace_bytes(m);
+    const SkinnyPlan pl = (m.dtype == LORY_F32) ? skinny_plan<float>(m) : skinny_plan<__hip_bfloat16>(m);
+    return align_up(sizeof(float) * (pl.part + pl.act), 256);
+}
+
+int dense_ffn_fwd(const Dims &m, const void *X, const void *Wbar, void *Y, void *ws, hipStream_t st)
+{
+    if (gemm_path(m)) return bf16_dense_ffn_fwd(m, X, Wbar, Y, ws, st);
+    if (m.dtype == LORY_F32) return skinny_ffn<float>(m, (const float *)X, (const float *)Wbar, (float *)Y, ws, st);
+    return skinny_ffn<__hip_bfloat16>(m, (const __hip_bfloat16 *)X, (const __hip_bfloat16 *)Wbar,
+                                      (__hip_bfloat16 *)Y, ws, st);
+}
+
+}  // namespace lory

@@ -23,6 +23,19 @@ int check_shape(const lory_shape *s)
     return LORY_OK;
 }
 
+// The inference entry points treat every sequence as one segment (T == L) of any length.
+int check_shape_infer(const lory_shape *s)
+{
+    if (!s) return LORY_ERR_NULL;
+    if (s->dtype != LORY_F32 && s->dtype != LORY_BF16) return LORY_ERR_DTYPE;
+    if (s->B <= 0 || s->L <= 0 || s->T <= 0 || s->d <= 0 || s->d_ff <= 0 || s->E <= 0)
+        return LORY_ERR_SHAPE;
+    if (s->T != s->L) return LORY_ERR_SHAPE;
+    if (s->E > 64 || s->d > 16384 || s->B > 65535) return LORY_ERR_SHAPE;
+    if (s->dtype == LORY_BF16 && (s->d % 64 != 0 || s->d_ff % 64 != 0)) return LORY_ERR_SHAPE;
+    return LORY_OK;
+}
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
@@ -69,6 +82,12 @@ int lory_merged_save_bytes(const lory_shape *shape, size_t *bytes_out)
 int lory_workspace_bytes(const lory_shape *shape, int pass, size_t *bytes_out)
 {
     if (!bytes_out) return LORY_ERR_NULL;
+    if (pass == LORY_PASS_DENSE) {
+        const int rci = check_shape_infer(shape);
+        if (rci != LORY_OK) return rci;
+        *bytes_out = lory::align_up(lory::dense_workspace_bytes(lory::make_dims(*shape)), 256);
+        return LORY_OK;
+    }
     const int rc = check_shape(shape);
     if (rc != LORY_OK) return rc;
     if (pass != LORY_PASS_FWD && pass != LORY_PASS_BWD) return LORY_ERR_SHAPE;
@@ -111,6 +130,42 @@ int lory_route_bwd(const lory_shape *shape, const void *R, const float *w, const
                         4.0 * m.S * m.d * m.E + rows * m.d,
                         2.0 * esz * rows * m.d + 4.0 * ((double)m.S * m.d + (double)m.d * m.E));
     return lory::route_bwd_launch(m, R, w, hbar, dw, dX, dR, accumulate_dR, (hipStream_t)stream);
+}
+
+int lory_prompt_merge(const lory_shape *shape, const void *X_prompt, const void *R, const void *Wg,
+                      const void *Wu, const void *Wd, float *w, void *Wbar, void *stream)
+{
+    const int rc = check_shape_infer(shape);
+    if (rc != LORY_OK) return rc;
+    if (!X_prompt || !R || !Wg || !Wu || !Wd || !w || !Wbar) return LORY_ERR_NULL;
+    if (!aligned16(X_prompt) || !aligned16(R) || !aligned16(Wg) || !aligned16(Wu) || !aligned16(Wd) ||
+        !aligned16(w) || !aligned16(Wbar))
+        return LORY_ERR_ALIGN;
+    const Dims m = lory::make_dims(*shape);
+    hipStream_t st = (hipStream_t)stream;
+    {
+        const double esz = (m.dtype == LORY_F32) ? 4.0 : 2.0;
+        lory::prof::Range r(st, lory::prof::kRoute, 2.0 * m.S * m.d * m.E + (double)m.tokens * m.d,
+                            esz * ((double)m.tokens * m.d + (double)m.d * m.E) + 4.0 * m.S * m.E);
+        const int rr = lory::route_launch(m, X_prompt, R, w, nullptr, nullptr, st);
+        if (rr != LORY_OK) return rr;
+    }
+    if (m.dtype == LORY_F32)
+        return lory::f32_merge_all(m, w, (const float *)Wg, (const float *)Wu, (const float *)Wd,
+                                   (float *)Wbar, st);
+    return lory::bf16_merge_all(m, w, Wg, Wu, Wd, Wbar, st);
+}
+
+int lory_dense_ffn_fwd(const lory_shape *shape, const void *X, const void *Wbar, void *Y,
+                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int rc = check_shape_infer(shape);
+    if (rc != LORY_OK) return rc;
+    if (!X || !Wbar || !Y || !workspace) return LORY_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Wbar) || !aligned16(Y) || !aligned16(workspace)) return LORY_ERR_ALIGN;
+    const Dims m = lory::make_dims(*shape);
+    if (workspace_bytes < lory::align_up(lory::dense_workspace_bytes(m), 256)) return LORY_ERR_WORKSPACE;
+    return lory::dense_ffn_fwd(m, X, Wbar, Y, workspace, (hipStream_t)stream);
 }
 
 int lory_merged_ffn_fwd(const lory_shape *shape, const void *X, const float *w, const void *Wg,

@@ -43,7 +43,7 @@ inline int launch_status()
 // ---- optional event timing per kernel class (profile.hip)
 namespace prof {
 enum Class { kRoute = 0, kMerge, kGemmGU, kSwigluFwd, kGemmDown, kGemmDA, kSwigluBwd, kGemmDX, kGemmDWGU, kGemmDWD, kScatter,
-             kDwReduce, kRouteBwd, kNumClasses };
+             kDwReduce, kRouteBwd, kDenseSkinny, kNumClasses };
 bool enabled();
 int set_enabled(int on);
 int read(lory_kernel_stat *out, int max_out, int *n_out);
@@ -78,7 +78,18 @@ int f32_ffn_bwd(const Dims &m, const float *X, const float *w, const float *Wg, 
                 float *dX, float *dWg, float *dWu, float *dWd, int accumulate, float *dw,
                 void *ws, hipStream_t st);
 
+int f32_merge_all(const Dims &m, const float *w, const float *Wg, const float *Wu, const float *Wd,
+                  float *Wbar, hipStream_t st);
+
+// ---- inference with prompt-only routing (infer.hip)
+size_t dense_workspace_bytes(const Dims &m);
+int dense_ffn_fwd(const Dims &m, const void *X, const void *Wbar, void *Y, void *ws, hipStream_t st);
+
 // ---- bf16 path (ffn_bf16.hip)
+int bf16_merge_all(const Dims &m, const float *w, const void *Wg, const void *Wu, const void *Wd,
+                   void *Wbar, hipStream_t st);
+size_t bf16_dense_workspace_bytes(const Dims &m);
+int bf16_dense_ffn_fwd(const Dims &m, const void *X, const void *Wbar, void *Y, void *ws, hipStream_t st);
 int set_slab_budget(size_t bytes);
 size_t bf16_workspace_bytes(const Dims &m, int pass);
 size_t bf16_merged_save_bytes(const Dims &m);

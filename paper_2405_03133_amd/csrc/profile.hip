@@ -26,7 +26,7 @@ std::vector<hipEvent_t> g_pool;
 
 const char *const kNames[kNumClasses] = {"route",     "merge",     "gemm_gate_up", "swiglu_fwd", "gemm_down",
                                          "gemm_dA",   "swiglu_bwd", "gemm_dX",   "gemm_dW_gate_up",
-                                         "gemm_dW_down", "scatter_dots", "dw_reduce", "route_bwd"};
+                                         "gemm_dW_down", "scatter_dots", "dw_reduce", "route_bwd", "dense_skinny"};
 
 hipEvent_t get_event()
 {

@@ -81,6 +81,38 @@ def test_route_bwd_validation():
     assert L.lory_route_bwd(None, F, F, F, F, F, F, 0, None) == lb.LORY_ERR_NULL
 
 
+def test_inference_entry_points_validation():
+    L = lb.lib()
+    F = FAKE
+    s = shape(L=37, T=37)                      # any prompt length, one segment per sequence
+    sp = ctypes.byref(s)
+    need = lb.lory_workspace_bytes(s, lb.LORY_PASS_DENSE)
+    assert need > 0 and need % 256 == 0
+    bad = ctypes.byref(shape(L=64, T=32))      # T != L
+    out = ctypes.c_size_t(5)
+    assert L.lory_workspace_bytes(bad, lb.LORY_PASS_DENSE, ctypes.byref(out)) == lb.LORY_ERR_SHAPE
+    assert out.value == 5
+    assert L.lory_prompt_merge(bad, F, F, F, F, F, F, F, None) == lb.LORY_ERR_SHAPE
+    assert L.lory_dense_ffn_fwd(bad, F, F, F, F, need, None) == lb.LORY_ERR_SHAPE
+    for i in range(7):
+        args = [F] * 7
+        args[i] = None
+        assert L.lory_prompt_merge(sp, *args, None) == lb.LORY_ERR_NULL
+        args[i] = F + 8
+        assert L.lory_prompt_merge(sp, *args, None) == lb.LORY_ERR_ALIGN
+    for i in range(4):
+        args = [F] * 4
+        args[i] = None
+        assert L.lory_dense_ffn_fwd(sp, *args, need, None) == lb.LORY_ERR_NULL
+        args[i] = F + 8
+        assert L.lory_dense_ffn_fwd(sp, *args, need, None) == lb.LORY_ERR_ALIGN
+    assert L.lory_dense_ffn_fwd(sp, F, F, F, F, need - 1, None) == lb.LORY_ERR_WORKSPACE
+    # bf16: d and d_ff granularity still applies, the token count does not
+    assert lb.lory_workspace_bytes(shape(dtype=lb.LORY_BF16, L=5, T=5, d=64, d_ff=128), lb.LORY_PASS_DENSE) > 0
+    assert L.lory_workspace_bytes(ctypes.byref(shape(dtype=lb.LORY_BF16, L=5, T=5, d=72)), lb.LORY_PASS_DENSE,
+                                  ctypes.byref(out)) == lb.LORY_ERR_SHAPE
+
+
 @pytest.mark.parametrize("dtype", [lb.LORY_F32, lb.LORY_BF16])
 def test_workspace_query_and_ffn_validation(dtype):
     L = lb.lib()

@@ -10,7 +10,7 @@ import torch
 
 from oracle import lory_oracle as orc
 from paper_2405_03133_amd import binding as lb
-from paper_2405_03133_amd.inputs import CONFIGS, LoryConfig, make_inputs, make_routing_weights
+from paper_2405_03133_amd.inputs import CONFIGS, LoryConfig, make_inputs, make_routing_weights, round_to_bf16
 
 pytestmark = pytest.mark.gpu
 
@@ -320,3 +320,71 @@ def test_whole_layer_gradient_fp32():
     compare(cfg, got, ref, ("dX", "dWg", "dWu", "dWd"), 2e-5)
     compare(cfg, got, ref, ("dR",), 1e-3)   # dR inherits the fp32 rounding of dw through a cancelling sum
     assert np.linalg.norm(ref["dR"]) > 0
+
+
+# ------------------------------------------------------------------ inference: prompt-only routing
+
+INFER_CASES = [
+    # (config of the expert stacks, prompt length, token counts of the generation-phase calls)
+    (LoryConfig("inf_f32", B=3, L=40, T=40, d=48, d_ff=72, E=5, dtype="f32", seed=51), 40, (1, 3, 8, 13)),
+    (LoryConfig("inf_f32_odd", B=2, L=7, T=7, d=50, d_ff=70, E=4, dtype="f32", seed=52), 7, (1, 9)),
+    (LoryConfig("inf_bf16", B=4, L=200, T=200, d=256, d_ff=704, E=8, dtype="bf16", seed=53), 200,
+     (1, 2, 8, 11, 64, 192)),
+    (LoryConfig("inf_bf16_wide", B=2, L=96, T=96, d=1024, d_ff=2816, E=32, dtype="bf16", seed=54), 96,
+     (1, 5, 256)),
+]
+
+
+@pytest.mark.parametrize("cfg,Lp,steps", INFER_CASES, ids=lambda v: v.name if isinstance(v, LoryConfig) else None)
+def test_prompt_only_routing_inference(cfg, Lp, steps):
+    """lory_prompt_merge + lory_dense_ffn_fwd against the oracle: routing on the mean of the whole
+    prompt (route with T = L), merged parameters by the definition, then the merged FFN on new tokens
+    (the oracle's ffn_fwd with one segment per sequence and the same routing weights)."""
+    print(f"[gpu] infer {cfg}", flush=True)
+    t = make_inputs(cfg, structured=True, with_dy=False)
+    tol = TOL[cfg.dtype]
+    X, R = to_dev(t["X"], cfg), to_dev(t["R"], cfg)
+    Wg, Wu, Wd = (to_dev(t[k], cfg) for k in ("Wg", "Wu", "Wd"))
+    w, Wbar = lb.lory_prompt_merge(X, R, Wg, Wu, Wd)
+    torch.cuda.synchronize()
+    ref_w = orc.route(t["X"], t["R"], Lp)["w"]
+    got_w = host(w)
+    assert rel_l2(got_w, ref_w) <= 1e-5
+    # merged parameters against the definition, from the GPU's own routing weights
+    D = cfg.d * cfg.d_ff
+    Wb = host(Wbar).reshape(3, cfg.B, D)
+    for i, k in enumerate(("Wg", "Wu", "Wd")):
+        ref = np.einsum("be,en->bn", got_w, t[k].astype(np.float64).reshape(cfg.E, D))
+        err = rel_l2(Wb[i], ref)
+        print(f"[parity] {cfg.name}: {k}_bar={err:.2e}", flush=True)
+        assert err <= (1e-5 if cfg.dtype == "f32" else 4e-3)
+    # generation phase: new tokens of several counts, the same merged parameters
+    for n_tok in steps:
+        rng = np.random.Generator(np.random.Philox(cfg.seed * 1000 + n_tok))
+        Xn_host = rng.standard_normal((cfg.B, n_tok, cfg.d)).astype(np.float32)
+        if cfg.dtype == "bf16":
+            Xn_host = round_to_bf16(Xn_host)
+        Xn = to_dev(Xn_host, cfg)
+        Y = lb.lory_dense_ffn_fwd(Xn, Wbar, cfg.d_ff)
+        torch.cuda.synchronize()
+        ref = orc.ffn_fwd(Xn_host, got_w, t["Wg"], t["Wu"], t["Wd"], n_tok)["Y"]
+        err = rel_l2(host(Y), ref)
+        print(f"[parity] {cfg.name}: {n_tok} tokens Y={err:.2e}", flush=True)
+        assert np.isfinite(err) and err <= tol, (cfg.name, n_tok, err)
+
+
+def test_prefill_with_saved_merged_parameters_feeds_decode(default_budget):
+    """lory_merged_ffn_fwd with T = L and Wbar_save leaves the same buffer lory_prompt_merge writes."""
+    cfg = LoryConfig("inf_prefill", B=2, L=128, T=128, d=128, d_ff=256, E=8, dtype="bf16", seed=55)
+    t = make_inputs(cfg, structured=True, with_dy=False)
+    X, R = to_dev(t["X"], cfg), to_dev(t["R"], cfg)
+    Wg, Wu, Wd = (to_dev(t[k], cfg) for k in ("Wg", "Wu", "Wd"))
+    w, Wbar = lb.lory_prompt_merge(X, R, Wg, Wu, Wd)
+    w2 = lb.lory_route(X, R, cfg.T, d_ff=cfg.d_ff)
+    save = lb.alloc_merged_save(lb.make_shape(cfg.B, cfg.L, cfg.T, cfg.d, cfg.d_ff, cfg.E, X.dtype))
+    Y = lb.lory_merged_ffn_fwd(X, w2, Wg, Wu, Wd, cfg.T, Wbar_save=save)
+    Yd = lb.lory_dense_ffn_fwd(X, Wbar, cfg.d_ff)
+    torch.cuda.synchronize()
+    assert torch.equal(w, w2)
+    assert torch.equal(save.view(torch.bfloat16), Wbar.reshape(-1))
+    assert rel_l2(host(Yd), host(Y)) <= 2e-3   # same GEMM kernels; SwiGLU fused against separate pass
