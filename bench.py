@@ -260,6 +260,11 @@ def main():
         default_launch = not (args.no_save or args.no_merged_save or args.slab_mb or args.grad_dtype != "bf16")
         roofline["traffic"] = TRAFFIC_BYTES.get((args.config, dominant)) if default_launch else None
 
+    # The paper's utilisation analysis (appendix on expert utilisation) calls an expert activated for
+    # an input when its routing weight exceeds 2/E; logged for the synthetic router, whose N(0, 0.02)
+    # weights give nearly uniform routing.
+    routing = {"experts_with_w_above_2_over_E": int((w > 2.0 / cfg.E).any(dim=0).sum().item()),
+               "mean_max_w": float(w.max(dim=1).values.mean().item())}
     gemm_tflops = cfg.gemm_flops(True) / (ms_per_step * 1e-3) / 1e12
     all_tflops = (cfg.gemm_flops(True) + cfg.merge_flops(4)) / (ms_per_step * 1e-3) / 1e12
     out = {
@@ -283,6 +288,7 @@ def main():
         "pct_bf16_mfma_peak_gemm_only": 100.0 * gemm_tflops / PEAK_BF16_TFLOPS,
         "pct_bf16_mfma_peak_with_merge": 100.0 * all_tflops / PEAK_BF16_TFLOPS,
         "roofline": roofline,
+        "routing": routing,
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:

@@ -73,6 +73,16 @@ CONFIGS: Dict[str, LoryConfig] = {
     "C3": LoryConfig("C3", B=8, L=4096, T=256, d=1024, d_ff=2816, E=32, dtype="bf16", seed=_BASE_SEED + 3),
     "C4": LoryConfig("C4", B=4, L=4096, T=256, d=2048, d_ff=5632, E=32, dtype="bf16", seed=_BASE_SEED + 4),
 }
+# One GPU's share of C4 under expert-wise model parallelism over 8 GPUs (paper Section 6): every
+# expert cut along d_ff, the same slice of all experts on one device.
+CONFIGS["C4_EP8"] = LoryConfig("C4_EP8", B=4, L=4096, T=256, d=2048, d_ff=704, E=32, dtype="bf16",
+                               seed=_BASE_SEED + 6)
+# The paper's own model shapes (Section 4.1 and its model table): 1.5B with 8/16/32 experts, 7B with 4.
+for _E in (8, 16, 32):
+    CONFIGS[f"P15_E{_E}"] = LoryConfig(f"P15_E{_E}", B=4, L=4096, T=256, d=1536, d_ff=4096, E=_E,
+                                       dtype="bf16", seed=_BASE_SEED + 7)
+CONFIGS["P7_E4"] = LoryConfig("P7_E4", B=4, L=4096, T=256, d=4096, d_ff=11008, E=4, dtype="bf16",
+                              seed=_BASE_SEED + 8)
 for _T in (64, 128, 256, 512, 1024):
     CONFIGS[f"C5_T{_T}"] = LoryConfig(f"C5_T{_T}", B=4, L=4096, T=_T, d=2048, d_ff=5632, E=16,
                                       dtype="bf16", seed=_BASE_SEED + 5)

@@ -36,7 +36,7 @@ def host(t):
 
 
 @pytest.mark.timeout(1500)
-@pytest.mark.parametrize("name", ["C4"])
+@pytest.mark.parametrize("name", ["C4", "C4_EP8", "C5_T64", "C5_T1024"])
 def test_full_size_sampled(name):
     cfg = CONFIGS[name]
     print(f"[full] generating {cfg}", flush=True)

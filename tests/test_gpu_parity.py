@@ -388,3 +388,24 @@ def test_prefill_with_saved_merged_parameters_feeds_decode(default_budget):
     assert torch.equal(w, w2)
     assert torch.equal(save.view(torch.bfloat16), Wbar.reshape(-1))
     assert rel_l2(host(Yd), host(Y)) <= 2e-3   # same GEMM kernels; SwiGLU fused against separate pass
+
+
+def test_prefix_routing_variant():
+    """The paper's prefix-routing ablation (Section 5.1): every segment of a sequence uses the merged
+    FFN chosen from the first segment.  On the GPU that is lory_prompt_merge on the first T tokens and
+    lory_dense_ffn_fwd over the whole sequence; the oracle is its ffn_fwd with the first segment's
+    routing weights repeated for every segment."""
+    cfg = LoryConfig("prefix", B=2, L=512, T=128, d=128, d_ff=320, E=8, dtype="bf16", seed=56)
+    t = make_inputs(cfg, structured=True, with_dy=False)
+    X, R = to_dev(t["X"], cfg), to_dev(t["R"], cfg)
+    Wg, Wu, Wd = (to_dev(t[k], cfg) for k in ("Wg", "Wu", "Wd"))
+    w, Wbar = lb.lory_prompt_merge(X[:, :cfg.T].contiguous(), R, Wg, Wu, Wd)
+    Y = lb.lory_dense_ffn_fwd(X, Wbar, cfg.d_ff)
+    torch.cuda.synchronize()
+    e0 = orc.route(t["X"][:, :cfg.T], t["R"], cfg.T)["w"]            # [B, E]: first segment on itself
+    assert rel_l2(host(w), e0) <= 1e-5
+    w_rep = np.repeat(host(w), cfg.N, axis=0)                         # the same row for all N segments
+    ref = orc.ffn_fwd(t["X"], w_rep, t["Wg"], t["Wu"], t["Wd"], cfg.T)["Y"]
+    err = rel_l2(host(Y), ref)
+    print(f"[parity] prefix routing Y={err:.2e}", flush=True)
+    assert err <= TOL["bf16"]
