@@ -211,24 +211,30 @@ struct ScatterParams {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kDotPitch = 528;  // bytes per segment row of a wave's LDS staging area (512 + 16)
+constexpr int kDotPitch = 272;  // bytes per segment row of a wave's LDS staging area (256 + 16)
 
 // One launch handles the experts e0 .. e0+31 (clipped to E).
 //   KBM  >= ceil(S / 16): static bound on the 16-segment K blocks
 //   EB16 =  ceil(window / 16): 16-expert blocks of the router-weight accumulators (1 or 2)
-// Per unit of 32 chunks a wave
-//   (1) loads the window's expert tiles once (B operand of the inner products),
-//   (2) walks the segments 16 at a time: loads their gradient chunks, parks them in its own LDS
-//       area, transposes them in registers and feeds the scatter MFMAs (K = segments), then
-//       re-reads them from LDS in the row-per-lane layout the inner-product MFMAs want
-//       (16x16x32, K = elements), so every gradient byte is fetched from memory once.
+// Work unit of a wavefront here: 16 consecutive 16-byte chunks (128 elements).  Lane
+// (chunk c = lane & 15, element half hh = (lane >> 4) & 1, segment half sh = lane >> 5) handles
+// elements 4hh..4hh+3 of chunk c: it loads them (8 bytes) from 8 segments per block of 16
+// segments, transposes them in registers into "8 segments of one element" (the B operand of
+// the scatter MFMA, K = segments, column = (c, hh)), and parks them in the wave's LDS area, from
+// where the inner-product MFMAs (16x16x32, K = elements) read them row-per-lane; every gradient
+// byte is fetched from memory once.  The small unit keeps a wave under 256 registers, so two
+// workgroups share a CU and hide each other's memory latency.
+// Per unit a wave
+//   (1) loads the window's expert chunks once (B operand of the inner products),
+//   (2) walks the segments 16 at a time (next block's loads in flight behind the MFMAs),
+//   (3) writes 32 experts x 128 elements of expert gradients.
 // Dynamic LDS: KB * 2 * 64 * 16 bytes of routing-weight operands + 4 * 16 * kDotPitch.
 template <int KBM, int EB16>
-__global__ __launch_bounds__(256, 1) void scatter_kernel(const ScatterParams p)
+__global__ __launch_bounds__(256, (KBM * EB16 <= 8) ? 2 : 1) void scatter_kernel(const ScatterParams p)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int ln = lane & 31, h = lane >> 5;
+    const int c = lane & 15, hh = (lane >> 4) & 1, sh = lane >> 5;
     const int KB = (p.S + 15) >> 4;
     uint4 *wtab = reinterpret_cast<uint4 *>(smem);  // [kb][hi/lo][lane]
     char *park = smem + (size_t)KB * 2 * 64 * 16 + wave * (16 * kDotPitch);
@@ -251,7 +257,7 @@ __global__ __launch_bounds__(256, 1) void scatter_kernel(const ScatterParams p)
     __syncthreads();
 
     const int Q = (p.rc.nr * p.rc.nc) >> 3;
-    const int units = (Q + 31) >> 5;
+    const int units = (Q + 15) >> 4;
     const int stride = gridDim.x * 4;
     const uint16_t *stack = p.stack + (size_t)p.e0 * p.rc.expert_stride;
 
@@ -264,14 +270,14 @@ __global__ __launch_bounds__(256, 1) void scatter_kernel(const ScatterParams p)
             for (int r = 0; r < 4; ++r) dots[a][b][r] = 0.f;
 
     for (int unit = blockIdx.x * 4 + wave; unit < units; unit += stride) {
-        const int q = unit * 32 + ln;
+        const int q = unit * 16 + c;
         const bool ok = q < Q;
 
-        // expert tiles of the window: lane (n = lane & 15, chunk group = lane >> 4)
-        Frag Bst[EB16][8];
+        // expert chunks of the window: lane (n = lane & 15, chunk 4*kq + (lane >> 4))
+        Frag Bst[EB16][4];
 #pragma unroll
-        for (int kq = 0; kq < 8; ++kq) {
-            const int qq = unit * 32 + 4 * kq + (lane >> 4);
+        for (int kq = 0; kq < 4; ++kq) {
+            const int qq = unit * 16 + 4 * kq + (lane >> 4);
             const bool okq = qq < Q;
             const long off2 = okq ? rect_offset(p.rc, qq) : 0;
 #pragma unroll
@@ -284,52 +290,58 @@ __global__ __launch_bounds__(256, 1) void scatter_kernel(const ScatterParams p)
             }
         }
 
-        f32x16 acc[8];
+        f32x16 acc[4];
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
 
-        Frag Rg[8];
+        // running pointer to this lane's first segment of the block being fetched
+        const uint16_t *gp = p.gslab + (size_t)q * 8 + 4 * hh + (size_t)(8 * sh) * p.seg_stride;
+        int seg0 = 8 * sh;
+        uint2 Rg[8];
+        auto load_grads = [&]() {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int seg = 8 * h + i;
-            if (ok && seg < p.S)
-                Rg[i].u = *reinterpret_cast<const uint4 *>(p.gslab + (size_t)seg * p.seg_stride + (size_t)q * 8);
-            else
-                Rg[i].u = make_uint4(0, 0, 0, 0);
-        }
+            for (int i = 0; i < 8; ++i) {
+                if (ok && seg0 + i < p.S)
+                    Rg[i] = *reinterpret_cast<const uint2 *>(gp + (size_t)i * p.seg_stride);
+                else
+                    Rg[i] = make_uint2(0, 0);
+            }
+            gp += (size_t)16 * p.seg_stride;
+            seg0 += 16;
+        };
+        load_grads();
 
 #pragma unroll
         for (int kb = 0; kb < KBM; ++kb) {
             if (kb < KB) {
-                Frag P[8];
+                Frag P[4];
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
-                    *reinterpret_cast<uint4 *>(park + (8 * h + i) * kDotPitch + ln * 16) = Rg[i].u;
-                transpose8x8(Rg, P);
-                if (kb + 1 < KB) {  // next 16 segments, in flight behind the MFMAs
+                    *reinterpret_cast<uint2 *>(park + (8 * sh + i) * kDotPitch + c * 16 + hh * 8) = Rg[i];
+                // P[j]: element 4hh + j of the chunk, segments 8sh .. 8sh+7 packed as 8 bf16
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int seg = 16 * (kb + 1) + 8 * h + i;
-                        if (ok && seg < p.S)
-                            Rg[i].u = *reinterpret_cast<const uint4 *>(p.gslab + (size_t)seg * p.seg_stride +
-                                                                       (size_t)q * 8);
-                        else
-                            Rg[i].u = make_uint4(0, 0, 0, 0);
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int ip = 0; ip < 4; ++ip) {
+                        const uint32_t a = (j >> 1) ? Rg[2 * ip].y : Rg[2 * ip].x;
+                        const uint32_t b = (j >> 1) ? Rg[2 * ip + 1].y : Rg[2 * ip + 1].x;
+                        P[j].w[ip] = (j & 1) ? __builtin_amdgcn_perm(b, a, 0x07060302u)
+                                             : __builtin_amdgcn_perm(b, a, 0x05040100u);
                     }
-                }
+                if (kb + 1 < KB) load_grads();  // next 16 segments, in flight behind the MFMAs
                 Frag whi, wlo;
                 whi.u = wtab[(kb * 2 + 0) * 64 + lane];
                 wlo.u = wtab[(kb * 2 + 1) * 64 + lane];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
+                for (int j = 0; j < 4; ++j) {
                     acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(whi.v, P[j].v, acc[j], 0, 0, 0);
                     acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wlo.v, P[j].v, acc[j], 0, 0, 0);
                 }
                 __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                for (int kq = 0; kq < 8; ++kq) {
+                for (int kq = 0; kq < 4; ++kq) {
                     Frag af;
                     af.u = *reinterpret_cast<const uint4 *>(park + (lane & 15) * kDotPitch +
                                                             (4 * kq + (lane >> 4)) * 16);
@@ -342,44 +354,35 @@ __global__ __launch_bounds__(256, 1) void scatter_kernel(const ScatterParams p)
             }
         }
 
+        // accumulator element r of lane (c, hh, sh): expert 8*(r>>2) + 4*sh + (r&3), elements 4hh..4hh+3 of chunk c
         if (ok) {
-            const long off = rect_offset(p.rc, q);
+            const long off = rect_offset(p.rc, q) + 4 * hh;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int e = 8 * (r >> 2) + 4 * h + (r & 3);
+                const int e = 8 * (r >> 2) + 4 * sh + (r & 3);
                 if (e >= Ewin) continue;
-                float v[8];
+                float v[4];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) v[j] = acc[j][r];
+                for (int j = 0; j < 4; ++j) v[j] = acc[j][r];
                 const size_t eoff = (size_t)(p.e0 + e) * p.rc.expert_stride + off;
                 if (p.grad_f32) {
                     float4 *dst = reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.dW) + eoff);
-                    float4 o0 = make_float4(v[0], v[1], v[2], v[3]);
-                    float4 o1 = make_float4(v[4], v[5], v[6], v[7]);
+                    float4 o = make_float4(v[0], v[1], v[2], v[3]);
                     if (p.accumulate) {
-                        const float4 c0 = dst[0], c1 = dst[1];
-                        o0.x += c0.x; o0.y += c0.y; o0.z += c0.z; o0.w += c0.w;
-                        o1.x += c1.x; o1.y += c1.y; o1.z += c1.z; o1.w += c1.w;
+                        const float4 cur = *dst;
+                        o.x += cur.x; o.y += cur.y; o.z += cur.z; o.w += cur.w;
                     }
-                    dst[0] = o0;
-                    dst[1] = o1;
-                } else {
-                    uint4 *dst = reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.dW) + eoff);
-                    if (p.accumulate) {
-                        const uint4 c = *dst;
-                        const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            v[2 * i] += __uint_as_float(cw[i] << 16);
-                            v[2 * i + 1] += __uint_as_float(cw[i] & 0xffff0000u);
-                        }
-                    }
-                    uint4 o;
-                    o.x = pack_bf16(v[0], v[1]);
-                    o.y = pack_bf16(v[2], v[3]);
-                    o.z = pack_bf16(v[4], v[5]);
-                    o.w = pack_bf16(v[6], v[7]);
                     *dst = o;
+                } else {
+                    uint2 *dst = reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(p.dW) + eoff);
+                    if (p.accumulate) {
+                        const uint2 cur = *dst;
+                        v[0] += __uint_as_float(cur.x << 16);
+                        v[1] += __uint_as_float(cur.x & 0xffff0000u);
+                        v[2] += __uint_as_float(cur.y << 16);
+                        v[3] += __uint_as_float(cur.y & 0xffff0000u);
+                    }
+                    *dst = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
                 }
             }
         }
