@@ -6,7 +6,8 @@ namespace k {
 
 namespace {
 // dw[s][e] = sum over slots of partials[slot][s][e].  One workgroup per segment row: thread
-// (e, g) adds slots g, g+16, ... in order, then the 16 group sums are added in order.
+// (e, g) adds slots g, g+16, ... along four interleaved chains (fixed order), then the 16 group
+// sums are added in order.
 __global__ __launch_bounds__(1024) void dw_reduce_kernel(const float *__restrict__ partials, int slots,
                                                          int rows, int cols, float *__restrict__ dw,
                                                          int S, int E)
@@ -14,10 +15,20 @@ __global__ __launch_bounds__(1024) void dw_reduce_kernel(const float *__restrict
     __shared__ float red[16][64];
     const int s = blockIdx.x;
     const int e = threadIdx.x & 63, g = threadIdx.x >> 6;
-    float acc = 0.f;
-    if (e < E)
-        for (int k = g; k < slots; k += 16) acc += partials[((size_t)k * rows + s) * cols + e];
-    red[g][e] = acc;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    if (e < E) {
+        const float *src = partials + (size_t)s * cols + e;
+        const size_t pitch = (size_t)rows * cols;
+        int k = g;
+        for (; k + 48 < slots; k += 64) {
+            a0 += src[(size_t)k * pitch];
+            a1 += src[(size_t)(k + 16) * pitch];
+            a2 += src[(size_t)(k + 32) * pitch];
+            a3 += src[(size_t)(k + 48) * pitch];
+        }
+        for (; k < slots; k += 16) a0 += src[(size_t)k * pitch];
+    }
+    red[g][e] = (a0 + a1) + (a2 + a3);
     __syncthreads();
     if (g == 0 && e < E) {
         float sum = 0.f;
@@ -74,8 +85,24 @@ hipError_t launch_scatter(hipStream_t st, const ms::ScatterParams &p, int grid)
     if (KB > 16 || p.e0 % 32 != 0 || p.e0 >= p.E) return hipErrorInvalidValue;
     const int win = (p.E - p.e0 < 32) ? (p.E - p.e0) : 32;
     const int eb16 = (win + 15) / 16;
-    const size_t lds = (size_t)KB * 2 * 64 * 16 + 4 * 16 * ms::kDotPitch;
-#define LORY_SCATTER(K, B) hipLaunchKernelGGL((ms::scatter_kernel<K, B>), dim3(grid), dim3(256), lds, st, p)
+    const size_t lds_main = (size_t)KB * 2 * 64 * 16 + 4 * 16 * ms::kDotPitch;
+#define LORY_SCATTER(K, B)                                                                            \
+    do {                                                                                              \
+        const size_t lds_red = (size_t)4 * K * B * 1024;                                              \
+        const size_t lds = lds_main > lds_red ? lds_main : lds_red;                                   \
+        auto kern = ms::scatter_kernel<K, B>;                                                         \
+        if (lds > 48 * 1024) {                                                                        \
+            static bool configured = false;                                                           \
+            if (!configured) {                                                                        \
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),              \
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize,        \
+                                                   160 * 1024);                                       \
+                if (e != hipSuccess) return e;                                                        \
+                configured = true;                                                                    \
+            }                                                                                         \
+        }                                                                                             \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, p);                                  \
+    } while (0)
 #define LORY_SCATTER_K(B)                          \
     switch (kbm_of(p.S)) {                         \
     case 1: LORY_SCATTER(1, B); break;             \

@@ -88,7 +88,7 @@ Plan make_plan(const Dims &m)
     if (re > b) b = re;
     p.slab_bwd = align_up(b, 256);
     k::scatter_partial_dims(p.Sc, m.E, &p.prow, &p.pcol);
-    p.partials = align_up((size_t)k::scatter_grid() * 4 * p.prow * p.pcol * sizeof(float), 256);
+    p.partials = align_up((size_t)k::scatter_grid() * p.prow * p.pcol * sizeof(float), 256);
     return p;
 }
 
@@ -431,8 +431,8 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
 
         int prow, pcol;
         k::scatter_partial_dims(S, m.E, &prow, &pcol);
-        prof::Range r(st, prof::kDwReduce, (double)grid * 4 * S * m.E, 4.0 * grid * 4 * prow * pcol);
-        LORY_TRY(k::launch_dw_reduce(st, partials, grid * 4, prow, pcol, dw + (size_t)s0 * m.E, S, m.E));
+        prof::Range r(st, prof::kDwReduce, (double)grid * S * m.E, 4.0 * grid * prow * pcol);
+        LORY_TRY(k::launch_dw_reduce(st, partials, grid, prow, pcol, dw + (size_t)s0 * m.E, S, m.E));
     }
     return LORY_OK;
 }

@@ -204,7 +204,7 @@ struct ScatterParams {
     Rect rc;
     int grad_f32;            // dW is fp32 (else bf16)
     int accumulate;          // add to dW instead of overwriting it
-    float *partials;         // [gridDim.x * 4][KBM*16][pcols] per-wave router-weight partial sums
+    float *partials;         // [gridDim.x][KBM*16][pcols] per-workgroup router-weight partial sums
     int pcols;               // columns of a partials row (>= E)
     int partials_add;        // add to the existing partials instead of overwriting them
 };
@@ -228,7 +228,8 @@ constexpr int kDotPitch = 272;  // bytes per segment row of a wave's LDS staging
 //   (1) loads the window's expert chunks once (B operand of the inner products),
 //   (2) walks the segments 16 at a time (next block's loads in flight behind the MFMAs),
 //   (3) writes 32 experts x 128 elements of expert gradients.
-// Dynamic LDS: KB * 2 * 64 * 16 bytes of routing-weight operands + 4 * 16 * kDotPitch.
+// Dynamic LDS: the larger of KB * 2 * 64 * 16 bytes of routing-weight operands + 4 * 16 * kDotPitch
+// and 4 * KBM * EB16 * 1024 bytes for the final reduction of the router-weight accumulators.
 template <int KBM, int EB16>
 __global__ __launch_bounds__(256, (KBM * EB16 <= 8) ? 2 : 1) void scatter_kernel(const ScatterParams p)
 {
@@ -388,23 +389,31 @@ __global__ __launch_bounds__(256, (KBM * EB16 <= 8) ? 2 : 1) void scatter_kernel
         }
     }
 
-    // per-wave partial sums of dw; a later kernel adds them up in slot order.
+    // Partial sums of dw per workgroup: the four waves' accumulators are added in wave order in
+    // LDS (which nobody needs any more), a later kernel adds the workgroups' slots in slot order.
     // 16x16 accumulator element r: row (segment) 4*(lane>>4) + r, column (expert) lane & 15.
-    const size_t slot = (size_t)blockIdx.x * 4 + wave;
-    float *part = p.partials + slot * (KBM * 16) * p.pcols;
+    constexpr int kPer = KBM * EB16 * 4 * 64;  // accumulator values of one wave
+    float *red = reinterpret_cast<float *>(smem);
+    __syncthreads();
 #pragma unroll
     for (int kb = 0; kb < KBM; ++kb)
 #pragma unroll
         for (int b = 0; b < EB16; ++b)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int seg = kb * 16 + 4 * (lane >> 4) + r;
-                const int e = p.e0 + b * 16 + (lane & 15);
-                if (e < p.pcols) {
-                    float *dst = part + (size_t)seg * p.pcols + e;
-                    *dst = p.partials_add ? (*dst + dots[kb][b][r]) : dots[kb][b][r];
-                }
-            }
+            for (int r = 0; r < 4; ++r) red[wave * kPer + ((kb * EB16 + b) * 4 + r) * 64 + lane] = dots[kb][b][r];
+    __syncthreads();
+    float *part = p.partials + (size_t)blockIdx.x * (KBM * 16) * p.pcols;
+    for (int idx = tid; idx < kPer; idx += 256) {
+        const float v = ((red[idx] + red[kPer + idx]) + red[2 * kPer + idx]) + red[3 * kPer + idx];
+        const int l = idx & 63, r = (idx >> 6) & 3, kbb = idx >> 8;
+        const int kb = kbb / EB16, b = kbb - kb * EB16;
+        const int seg = kb * 16 + 4 * (l >> 4) + r;
+        const int e = p.e0 + b * 16 + (l & 15);
+        if (e < p.pcols) {
+            float *dst = part + (size_t)seg * p.pcols + e;
+            *dst = p.partials_add ? (*dst + v) : v;
+        }
+    }
 }
 
 }  // namespace ms
