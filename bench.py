@@ -49,6 +49,9 @@ def parse_args():
                     help="do not hand the forward's merged parameters to the backward (it re-merges)")
     ap.add_argument("--slab-mb", type=int, default=0)
     ap.add_argument("--verbose", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay one captured HIP graph of the step instead of launching every step eagerly "
+                         "(measured equal: the host stays ahead of the GPU either way)")
     ap.add_argument("--mode", default="train", choices=["train", "infer"],
                     help="train: the headline step (default).  infer: prompt-only routing, one merge per "
                          "sequence from a prompt of L tokens, then decode steps of one token per sequence")
@@ -215,12 +218,23 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # The step is a fixed sequence of about twenty launches on one stream; it can be captured once
+    # into a HIP graph and replayed (the library neither allocates nor synchronises, and records no
+    # memset nodes).
+    run = step
+    if args.graph:
+        step()                      # first call sets the kernels' LDS attributes (not capturable work)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run = graph.replay
     for _ in range(args.warmup):
-        step()
+        run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
@@ -282,7 +296,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} L={cfg.L} T={cfg.T} d={cfg.d} d_ff={cfg.d_ff} E={cfg.E} "
                                f"{cfg.dtype} route+fwd+bwd+route_bwd, grad_dtype={args.grad_dtype}, "
-                               f"save_GU={not args.no_save}, save_merged={Wbar is not None}",
+                               f"save_GU={not args.no_save}, save_merged={Wbar is not None}, "
+                               f"hip_graph={args.graph}",
                    "tokens": cfg.tokens, "segments": cfg.S},
         "gemm_tflops": gemm_tflops,
         "pct_bf16_mfma_peak_gemm_only": 100.0 * gemm_tflops / PEAK_BF16_TFLOPS,

@@ -409,3 +409,49 @@ def test_prefix_routing_variant():
     err = rel_l2(host(Y), ref)
     print(f"[parity] prefix routing Y={err:.2e}", flush=True)
     assert err <= TOL["bf16"]
+
+
+def test_step_replayed_from_a_hip_graph_matches_eager(default_budget):
+    """bench.py times a captured graph of the step; every replay must reproduce the eager results
+    bit for bit (the library enqueues kernels only: no allocation, no synchronisation, no memsets)."""
+    cfg = LoryConfig("graph", B=2, L=512, T=128, d=256, d_ff=512, E=8, dtype="bf16", seed=61)
+    t = make_inputs(cfg, structured=True)
+    X, R = to_dev(t["X"], cfg), to_dev(t["R"], cfg)
+    Wg, Wu, Wd = (to_dev(t[k], cfg) for k in ("Wg", "Wu", "Wd"))
+    dY = to_dev(t["dY"], cfg)
+    shape = lb.make_shape(cfg.B, cfg.L, cfg.T, cfg.d, cfg.d_ff, cfg.E, X.dtype)
+    ws_f, ws_b = lb.alloc_workspace(shape, lb.LORY_PASS_FWD), lb.alloc_workspace(shape, lb.LORY_PASS_BWD)
+    w = torch.empty((cfg.S, cfg.E), dtype=torch.float32, device="cuda")
+    hbar = torch.empty((cfg.S, cfg.d), dtype=torch.float32, device="cuda")
+    G = torch.empty((cfg.tokens, cfg.d_ff), dtype=X.dtype, device="cuda")
+    U = torch.empty_like(G)
+    Wbar = lb.alloc_merged_save(shape)
+    Y, dX = torch.empty_like(X), torch.empty_like(X)
+    dWg, dWu, dWd = torch.empty_like(Wg), torch.empty_like(Wu), torch.empty_like(Wd)
+    dw = torch.empty_like(w)
+    dR = torch.empty((cfg.d, cfg.E), dtype=torch.float32, device="cuda")
+    outs = (w, hbar, Y, dX, dWg, dWu, dWd, dw, dR)
+
+    def step():
+        lb.lory_route(X, R, cfg.T, w=w, hbar=hbar, d_ff=cfg.d_ff)
+        lb.lory_merged_ffn_fwd(X, w, Wg, Wu, Wd, cfg.T, Y=Y, G_save=G, U_save=U, workspace=ws_f, Wbar_save=Wbar)
+        lb.lory_merged_ffn_bwd(X, w, Wg, Wu, Wd, dY, cfg.T, G_save=G, U_save=U, dX=dX, dWg=dWg, dWu=dWu,
+                               dWd=dWd, dw=dw, grad_dtype=X.dtype, workspace=ws_b, Wbar_save=Wbar)
+        lb.lory_route_bwd(R, w, hbar, dw, dX, cfg.T, dR=dR, d_ff=cfg.d_ff)
+
+    step()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for o in outs:
+            o.fill_(float("nan")) if o.dtype.is_floating_point else o.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, ref in zip(outs, eager):
+            assert torch.equal(o, ref), rep
+        step()                      # eager work between replays
+        torch.cuda.synchronize()
