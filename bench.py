@@ -29,10 +29,10 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 # merged parameters saved, default slab budget).
 TRAFFIC_BYTES = {
     ("C4", "merge"): 2.215e9,
-    ("C4", "scatter_dots"): 3.009e9,
+    ("C4", "scatter_dots"): 2.967e9,
     ("C4", "gemm_gate_up"): 3.477e9,
     ("C4", "gemm_dX"): 3.393e9,
-    ("C4", "gemm_dW_gate_up"): 6.040e9,
+    ("C4", "gemm_dW_gate_up"): 6.039e9,
 }
 
 
