@@ -191,36 +191,43 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
         n0 = nt * BNS;
     };
 
-    // origin (in elements) of the tile the load stream is currently in
-    int ld_tile = -1;
+    // The A and the B operand of a K step are fetched at different times (see step()), so each
+    // load stream keeps the origin (in elements) of the tile it is currently in.
+    int ldA_tile = -1, ldB_tile = -1;
     long tileA = 0, tileB = 0;
-    int ld_batch = 0;
-    auto enter_tile = [&](int i) {
+    int ldA_batch = 0, ldB_batch = 0;
+    auto enter_tile_A = [&](int i) {
         int m0, n0;
-        tile_coords(i, ld_batch, m0, n0);
+        tile_coords(i, ldA_batch, m0, n0);
         tileA = A_MC ? (long)m0 : (long)m0 * p.lda[0];
+        ldA_tile = i;
+    };
+    auto enter_tile_B = [&](int i) {
+        int m0, n0;
+        tile_coords(i, ldB_batch, m0, n0);
         tileB = B_NC ? (long)n0 : (long)n0 * p.ldb[0];
-        ld_tile = i;
+        ldB_tile = i;
     };
 
-    // One of the 8 direct loads this wave contributes to K step g of its stream:
-    // i < 4 -> A chunk i, else B chunk i - 4.
-    // (gsrc = K step whose operands are fetched, gslot = K step whose ring slot receives them)
-    auto issue_one = [&](int gsrc, int gslot, int i) {
+    // The 4 + 4 direct loads this wave contributes to K step gsrc of its stream (A chunk i, B
+    // chunk j); gslot = K step whose ring slot receives them.
+    auto issue_A = [&](int gsrc, int gslot, int i) {
         const int t = gsrc % total;
         const int src = (NSRC == 2) ? (t / ktiles) : 0;
         const int ks = t % ktiles;
         const uint32_t stage = lds0 + (gslot & (kStages - 1)) * kStageBytes + wave_u * 4096;
-        if (i < 4) {
-            const uint16_t *a = p.A[src] + (size_t)ld_batch * p.a_batch[src] + tileA + ks * kstepA;
-            dma16(a + offA[i], stage + i * 1024);
-        } else {
-            const int j = i - 4;
-            const int set = (NSET == 2) ? ((wave * 4 + j) >> 3) : 0;  // 8 KB = 8 wave-loads per set
-            const int bi = (NSRC == 2) ? src : set;
-            const uint16_t *b = p.B[bi] + (size_t)ld_batch * p.b_batch[bi] + tileB + ks * kstepB;
-            dma16(b + offB[j], stage + kOperandBytes + j * 1024);
-        }
+        const uint16_t *a = p.A[src] + (size_t)ldA_batch * p.a_batch[src] + tileA + ks * kstepA;
+        dma16(a + offA[i], stage + i * 1024);
+    };
+    auto issue_B = [&](int gsrc, int gslot, int j) {
+        const int t = gsrc % total;
+        const int src = (NSRC == 2) ? (t / ktiles) : 0;
+        const int ks = t % ktiles;
+        const uint32_t stage = lds0 + (gslot & (kStages - 1)) * kStageBytes + wave_u * 4096;
+        const int set = (NSET == 2) ? ((wave * 4 + j) >> 3) : 0;  // 8 KB = 8 wave-loads per set
+        const int bi = (NSRC == 2) ? src : set;
+        const uint16_t *b = p.B[bi] + (size_t)ldB_batch * p.b_batch[bi] + tileB + ks * kstepB;
+        dma16(b + offB[j], stage + kOperandBytes + j * 1024);
     };
 
     f32x16 acc[NSET][MI][NI];
@@ -237,9 +244,12 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
 
     for (int g = 0; g < kStages - 1; ++g) {
         const int gsrc = g < G ? g : G - 1;
-        if (gsrc / total != ld_tile) enter_tile(gsrc / total);
+        if (gsrc / total != ldA_tile) enter_tile_A(gsrc / total);
+        if (gsrc / total != ldB_tile) enter_tile_B(gsrc / total);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) issue_one(gsrc, g, i);
+        for (int i = 0; i < 4; ++i) issue_A(gsrc, g, i);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) issue_B(gsrc, g, j);
     }
 
     // Fragment f of a 16-wide K slice: f < 4 -> A rows block f, else B columns block f - 4
@@ -273,22 +283,34 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
 #pragma unroll
     for (int f = 0; f < 8; ++f) load_frag(smem, 0, f, a0, b0);
 
-    // One K step.  The code is the same for every step: past the end of the stream the refill
-    // simply re-fetches the last K step into the ring slot that has just become free and the
-    // fragment prefetch reads a slot nobody will use, so there is exactly one group of 8 loads
-    // in flight per step and "all but the newest group have landed" (vmcnt(8)) always means
-    // "step g+1 is complete".
-    // EXTRA: store instructions of the previous tile's epilogue that were issued after the loads
-    // of step g+1 and may therefore still be pending (loads and stores share vmcnt and retire
-    // in order); only non-zero for the first two steps of a tile.
-    auto step = [&](int g, int extra_now) {
+    // One K step g.  Its 32 MFMA slots also carry the LDS fragment reads of the next slice (even
+    // slots) and this wave's eight direct loads for the ring, one every fourth slot, spread over
+    // the whole step: the four waves issue theirs at the same time, and the memory pipeline takes
+    // about 16 cycles per load, so loads in adjacent slots (as when all eight sat in one half
+    // step) stalled the waves for longer than the MFMAs they hide behind.  (Giving every wave
+    // slots of its own was tried: the wave-dependent branches cost far more than they saved.)
+    //   first half:  A chunks of step g+2 (into the slot step g-2 left at the previous barrier)
+    //   second half: B chunks of step g+3 (into the slot step g-1 left at this step's barrier)
+    // The B operand is the one that streams from HBM, hence the longer lead.  Across a tile
+    // boundary the A chunks that the next tile's first step would issue are issued half a step
+    // early, in the last step of the tile (after_last), so that everything the next tile's first
+    // two steps wait for is older than the epilogue's stores: loads and stores share vmcnt and
+    // retire in order, and a wait may only leave younger operations pending.
+    // Past the end of the stream the loads re-fetch the last K step into slots nobody reads, so
+    // "all but the newest 8 loads have landed" (vmcnt(8)) always means "step g+1 is complete".
+    // extra_now: store instructions of the previous tile's epilogue that may still be pending
+    // (only non-zero for the first two steps of a tile).
+    auto step = [&](int g, int extra_now, bool first_of_tile, bool last_of_tile) {
         const char *la = smem + (g & (kStages - 1)) * kStageBytes;
         const char *ln = smem + ((g + 1) & (kStages - 1)) * kStageBytes;
+        const int srcA = (g + 2 < G) ? (g + 2) : (G - 1);
+        if (!first_of_tile && srcA / total != ldA_tile) enter_tile_A(srcA / total);
 #pragma unroll
         for (int sl = 0; sl < 16; ++sl) {
             const int i = sl >> 2, q = sl & 3;
             acc[q / NI][i][q % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0[q], a0[i], acc[q / NI][i][q % NI], 0, 0, 0);
             if ((sl & 1) == 0) load_frag(la, 1, sl >> 1, a1, b1);
+            if (!first_of_tile && (sl & 3) == 1) issue_A(srcA, g + 2, sl >> 2);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (extra_now == 32)
@@ -298,16 +320,16 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
         else
             wait_vmcnt<8>();
         ring_barrier();
-        const int gsrc = (g + kStages - 1 < G) ? (g + kStages - 1) : (G - 1);  // K step to fetch
-        if (gsrc / total != ld_tile) enter_tile(gsrc / total);
+        const int srcB = (g + 3 < G) ? (g + 3) : (G - 1);  // K step to fetch
+        if (srcB / total != ldB_tile) enter_tile_B(srcB / total);
+        if (last_of_tile && srcB / total != ldA_tile) enter_tile_A(srcB / total);
 #pragma unroll
         for (int sl = 0; sl < 16; ++sl) {
             const int i = sl >> 2, q = sl & 3;
             acc[q / NI][i][q % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1[q], a1[i], acc[q / NI][i][q % NI], 0, 0, 0);
-            if ((sl & 1) == 0)
-                load_frag(ln, 0, sl >> 1, a0, b0);
-            else
-                issue_one(gsrc, g + kStages - 1, sl >> 1);
+            if ((sl & 1) == 0) load_frag(ln, 0, sl >> 1, a0, b0);
+            if ((sl & 3) == 1) issue_B(srcB, g + 3, sl >> 2);
+            if (last_of_tile && (sl & 3) == 3) issue_A(srcB, g + 3, sl >> 2);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -368,7 +390,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
         zero_acc();
         // the first two K steps of a tile run while the previous tile's stores drain
         const int relaxed = (tile_i > 0) ? 2 : 0;
-        for (int t = 0; t < total; ++t, ++g) step(g, t < relaxed ? extra : 0);
+        for (int t = 0; t < total; ++t, ++g) step(g, t < relaxed ? extra : 0, t == 0, t == total - 1);
         epilogue(tile_i);
     }
     wait_vmcnt<0>();  // no direct load may still be writing LDS when the workgroup retires
