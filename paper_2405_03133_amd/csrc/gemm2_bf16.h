@@ -372,7 +372,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
                     const int idx = it * 64 + lane;
                     const int row = idx / CP, c = idx % CP;
                     const u32x4 val = *reinterpret_cast<const u32x4 *>(stg + row * (WN * 2) + ((c ^ (row & (CP - 1))) << 4));
-                    *reinterpret_cast<u32x4 *>(epi.ptr(o, batch, m0 + wm0 + i * 32 + row, n0 + wn0 + c * 8)) = val;
+                    // streamed output: non-temporal, so that it does not push the operands that later
+                    // tiles share (activations of the segment) out of the caches
+                    __builtin_nontemporal_store(
+                        val, reinterpret_cast<u32x4 *>(epi.ptr(o, batch, m0 + wm0 + i * 32 + row, n0 + wn0 + c * 8)));
                 }
                 __builtin_amdgcn_wave_barrier();
             }
