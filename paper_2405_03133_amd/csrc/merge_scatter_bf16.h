@@ -383,7 +383,11 @@ __global__ __launch_bounds__(256, (KBM * EB16 <= 8) ? 2 : 1) void scatter_kernel
                         v[2] += __uint_as_float(cur.y << 16);
                         v[3] += __uint_as_float(cur.y & 0xffff0000u);
                     }
-                    *dst = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
+                    typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
+                    u32x2v ov;
+                    ov.x = pack_bf16(v[0], v[1]);
+                    ov.y = pack_bf16(v[2], v[3]);
+                    __builtin_nontemporal_store(ov, reinterpret_cast<u32x2v *>(dst));
                 }
             }
         }
