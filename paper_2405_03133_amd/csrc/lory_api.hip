@@ -109,7 +109,7 @@ int lory_route(const lory_shape *shape, const void *X, const void *R, float *w, 
     const double esz = (m.dtype == LORY_F32) ? 4.0 : 2.0;
     lory::prof::Range r((hipStream_t)stream, lory::prof::kRoute, 2.0 * m.S * m.d * m.E + (double)m.tokens * m.d,
                         esz * ((double)m.tokens * m.d + (double)m.d * m.E) + 4.0 * m.S * m.E);
-    return lory::route_launch(m, X, R, w, hbar_opt, nullptr, (hipStream_t)stream);
+    return lory::route_launch(m, X, R, w, hbar_opt, (hipStream_t)stream);
 }
 
 int lory_route_bwd(const lory_shape *shape, const void *R, const float *w, const float *hbar,
@@ -147,7 +147,7 @@ int lory_prompt_merge(const lory_shape *shape, const void *X_prompt, const void 
         const double esz = (m.dtype == LORY_F32) ? 4.0 : 2.0;
         lory::prof::Range r(st, lory::prof::kRoute, 2.0 * m.S * m.d * m.E + (double)m.tokens * m.d,
                             esz * ((double)m.tokens * m.d + (double)m.d * m.E) + 4.0 * m.S * m.E);
-        const int rr = lory::route_launch(m, X_prompt, R, w, nullptr, nullptr, st);
+        const int rr = lory::route_launch(m, X_prompt, R, w, nullptr, st);
         if (rr != LORY_OK) return rr;
     }
     if (m.dtype == LORY_F32)

@@ -61,9 +61,7 @@ private:
 }  // namespace prof
 
 // ---- routing (route.hip)
-int route_launch(const Dims &m, const void *X, const void *R, float *w, float *hbar,
-                 float *hbar_scratch, hipStream_t st);
-size_t route_scratch_bytes(const Dims &m);
+int route_launch(const Dims &m, const void *X, const void *R, float *w, float *hbar, hipStream_t st);
 
 // ---- routing backward (route_bwd.hip)
 int route_bwd_launch(const Dims &m, const void *R, const float *w, const float *hbar, const float *dw,

@@ -161,8 +161,7 @@ int launch_route(const Dims &m, const void *X, const void *R, float *w, float *h
 
 }  // namespace
 
-int route_launch(const Dims &m, const void *X, const void *R, float *w, float *hbar,
-                 float * /*unused*/, hipStream_t st)
+int route_launch(const Dims &m, const void *X, const void *R, float *w, float *hbar, hipStream_t st)
 {
     static_assert(kMaxE == 64, "logit stage assumes E <= 64");
     if (m.dtype == LORY_F32) {
@@ -172,7 +171,5 @@ int route_launch(const Dims &m, const void *X, const void *R, float *w, float *h
     if (m.d % Vec<__hip_bfloat16>::n == 0) return launch_route<__hip_bfloat16, true>(m, X, R, w, hbar, st);
     return launch_route<__hip_bfloat16, false>(m, X, R, w, hbar, st);
 }
-
-size_t route_scratch_bytes(const Dims &) { return 0; }
 
 }  // namespace lory
