@@ -8,11 +8,12 @@ namespace k {
 hipError_t launch_dwgu(hipStream_t st, const gemm::Params &p, const EpiStore2 &e)
 {
     // A = X_s stored [T][d] (M contiguous), B = dG_s / dU_s stored [T][d_ff] (N contiguous).
-    // The contraction is only T long, so the kernel is bound by writing its output; two
-    // single-set launches with square tiles and several workgroups per CU do better than one
-    // launch that shares X between the two operand sets.
-    if (gemm2::fits<2, 1>(p)) return gemm2::launch<2, 1, true, true>(p, e, st);
-    if (p.N % 128 == 0 || p.N % 64 != 0) {
+    // The contraction is only T long, so the kernel is bound by writing its output: sharing X
+    // between the two operand sets saves little, and two single-set launches (256-wide rows of
+    // output per wave pair, half as many stores in flight per tile) measured a little faster.
+    const bool split = gemm2::fits<1, 1>(p) || !gemm2::fits<2, 1>(p);
+    if (!split) return gemm2::launch<2, 1, true, true>(p, e, st);
+    if (gemm2::fits<1, 1>(p) || p.N % 128 == 0 || p.N % 64 != 0) {
         gemm::Params q = p;
         EpiStore e0 = {e.C0, e.c_batch, e.ldc};
         hipError_t rc = launch_dwd(st, q, e0);
