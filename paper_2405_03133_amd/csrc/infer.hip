@@ -13,8 +13,9 @@
 //   consecutive columns with one 16-byte load per lane and row; the 4 wavefronts
 //   of a workgroup take interleaved rows of its K slice; x is staged in LDS as
 //   fp32; partial sums go to [K split][sequence][matrix][token][n] in the
-//   workspace and are added in split order by the finishing kernels (SwiGLU for
-//   gate/up, store for down) => bit-reproducible.
+//   workspace and are added in split order by their consumer (the down pass forms
+//   the SwiGLU activation from the gate/up parts while staging its x; a small
+//   finishing kernel adds the down parts and stores Y) => bit-reproducible.
 #include "lory_internal.h"
 
 #include <hip/hip_bf16.h>
@@ -69,14 +70,17 @@ template <> struct Ld<__hip_bfloat16> {
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(__hip_bfloat16 v) { return Ld<__hip_bfloat16>::one(&v); }
 
-// TW: storage type of the weights.  TX: type of x (TW for the layer input, float for the
-// activation between the two phases).  MT tokens, NMAT matrices sharing x (2 = gate and up),
-// VEC columns per lane (Ld<TW>::vec, or 1 when N is not a multiple of it).
-//   x:    [B][x_rows][K]   (token t of sequence b at x + (b * x_rows + t) * K)
+// TW: storage type of the weights.  MT tokens, NMAT matrices sharing x (2 = gate and up), VEC
+// columns per lane (Ld<TW>::vec, or 1 when N is not a multiple of it).
+//   x:    NMAT == 2: the layer input [B][x_rows][K] of type TW (token t of sequence b at
+//         x + (b * x_rows + t) * K).  NMAT == 1 (down projection): x is the SwiGLU activation,
+//         which is formed on the fly from the gate/up partial sums gu [gu_ks][B][2][MT][K]:
+//         silu(sum of gate parts) * (sum of up parts), parts added in split order.
 //   W0/1: [B][K][N]
 //   part: [ksplit][B][NMAT][MT][N] fp32
-template <typename TW, typename TX, int MT, int NMAT, int VEC>
-__global__ __launch_bounds__(kSkThreads) void skinny_kernel(const TX *__restrict__ x, long x_rows,
+template <typename TW, int MT, int NMAT, int VEC>
+__global__ __launch_bounds__(kSkThreads) void skinny_kernel(const TW *__restrict__ x, long x_rows,
+                                                            const float *__restrict__ gu, int gu_ks,
                                                             const TW *__restrict__ W0,
                                                             const TW *__restrict__ W1, float *__restrict__ part,
                                                             int K, int N, int slice)
@@ -91,7 +95,17 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const TX *__restrict
 
     for (int i = tid; i < MT * (k1 - k0); i += kSkThreads) {
         const int t = i / (k1 - k0), k = i - t * (k1 - k0);
-        xs[t * kMaxSlice + k] = to_f32(x[((size_t)b * x_rows + t) * K + k0 + k]);
+        if constexpr (NMAT == 2) {
+            xs[t * kMaxSlice + k] = to_f32(x[((size_t)b * x_rows + t) * K + k0 + k]);
+        } else {
+            float g = 0.f, u = 0.f;
+            for (int ks = 0; ks < gu_ks; ++ks) {
+                const float *pp = gu + (((size_t)ks * B + b) * 2) * MT * K + k0 + k;
+                g += pp[(size_t)t * K];
+                u += pp[((size_t)MT + t) * K];
+            }
+            xs[t * kMaxSlice + k] = g / (1.0f + expf(-g)) * u;
+        }
     }
     __syncthreads();
 
@@ -151,25 +165,6 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const TX *__restrict
         }
 }
 
-// act[b][t][n] = silu(g) * u with g, u summed over the K splits.   part: [ks][B][2][mt][N]
-__global__ void skinny_finish_gu_kernel(const float *__restrict__ part, float *__restrict__ act, int ksplit,
-                                        int B, int mt, int N)
-{
-    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long total = (long)B * mt * N;
-    if (i >= total) return;
-    const int n = (int)(i % N);
-    const int t = (int)((i / N) % mt);
-    const int b = (int)(i / ((long)N * mt));
-    float g = 0.f, u = 0.f;
-    for (int ks = 0; ks < ksplit; ++ks) {
-        const float *p = part + (((size_t)ks * B + b) * 2) * mt * N;
-        g += p[(size_t)t * N + n];
-        u += p[((size_t)mt + t) * N + n];
-    }
-    act[i] = g / (1.0f + expf(-g)) * u;
-}
-
 // Y[b][t0 + t][j] = sum over the K splits.   part: [ks][B][1][mt][N]
 template <typename T>
 __global__ void skinny_finish_down_kernel(const float *__restrict__ part, T *__restrict__ Y, int ksplit, int B,
@@ -202,8 +197,8 @@ int choose_ksplit(int K, int N, int B, int vec)
 struct SkinnyPlan {
     int vec1, vec2;     // columns per lane in the two phases
     int ks1, ks2;       // K splits
-    size_t part;        // floats of the partial-sum area
-    size_t act;         // floats of the activation area
+    size_t part1;       // floats of the gate/up partial sums
+    size_t part2;       // floats of the down-projection partial sums
 };
 
 template <typename T>
@@ -214,20 +209,18 @@ SkinnyPlan skinny_plan(const Dims &m)
     p.vec2 = (m.d % Ld<T>::vec == 0) ? Ld<T>::vec : 1;
     p.ks1 = choose_ksplit(m.d, m.dff, m.B, p.vec1);
     p.ks2 = choose_ksplit(m.dff, m.d, m.B, p.vec2);
-    const size_t p1 = (size_t)p.ks1 * m.B * 2 * kMaxTok * m.dff;
-    const size_t p2 = (size_t)p.ks2 * m.B * kMaxTok * m.d;
-    p.part = p1 > p2 ? p1 : p2;
-    p.act = (size_t)m.B * kMaxTok * m.dff;
+    p.part1 = (size_t)p.ks1 * m.B * 2 * kMaxTok * m.dff;
+    p.part2 = (size_t)p.ks2 * m.B * kMaxTok * m.d;
     return p;
 }
 
-template <typename TW, typename TX, int NMAT, int VEC>
-void launch_skinny(hipStream_t st, int mt, dim3 grid, const TX *x, long x_rows, const TW *W0, const TW *W1,
-                   float *part, int K, int N, int slice)
+template <typename TW, int NMAT, int VEC>
+void launch_skinny(hipStream_t st, int mt, dim3 grid, const TW *x, long x_rows, const float *gu, int gu_ks,
+                   const TW *W0, const TW *W1, float *part, int K, int N, int slice)
 {
-#define LORY_SK(M)                                                                                           \
-    hipLaunchKernelGGL((skinny_kernel<TW, TX, M, NMAT, VEC>), grid, dim3(kSkThreads), 0, st, x, x_rows, W0, \
-                       W1, part, K, N, slice)
+#define LORY_SK(M)                                                                                          \
+    hipLaunchKernelGGL((skinny_kernel<TW, M, NMAT, VEC>), grid, dim3(kSkThreads), 0, st, x, x_rows, gu,    \
+                       gu_ks, W0, W1, part, K, N, slice)
     switch (mt) {
     case 1: LORY_SK(1); break;
     case 2: LORY_SK(2); break;
@@ -245,8 +238,8 @@ template <typename T>
 int skinny_ffn(const Dims &m, const T *X, const T *Wbar, T *Y, void *ws, hipStream_t st)
 {
     const SkinnyPlan pl = skinny_plan<T>(m);
-    float *part = (float *)ws;
-    float *act = part + pl.part;
+    float *part1 = (float *)ws;
+    float *part2 = part1 + pl.part1;
     const T *Wg = Wbar, *Wu = Wbar + (size_t)m.B * m.D, *Wd = Wbar + (size_t)2 * m.B * m.D;
     const int slice1 = (m.d + pl.ks1 - 1) / pl.ks1, slice2 = (m.dff + pl.ks2 - 1) / pl.ks2;
     const int ks1 = (m.d + slice1 - 1) / slice1, ks2 = (m.dff + slice2 - 1) / slice2;
@@ -255,30 +248,28 @@ int skinny_ffn(const Dims &m, const T *X, const T *Wbar, T *Y, void *ws, hipStre
         const int mt = (m.L - t0 < kMaxTok) ? (m.L - t0) : kMaxTok;
         prof::Range r(st, prof::kDenseSkinny, 6.0 * m.B * mt * (double)m.D,
                       esz * (3.0 * m.B * m.D + 2.0 * m.B * mt * m.d));
-        // phase 1: gate and up partial sums, then SwiGLU
+        // phase 1: gate and up partial sums
         {
             const dim3 grid((m.dff + 64 * pl.vec1 - 1) / (64 * pl.vec1), ks1, m.B);
             const T *x = X + (size_t)t0 * m.d;
             if (pl.vec1 == 1)
-                launch_skinny<T, T, 2, 1>(st, mt, grid, x, m.L, Wg, Wu, part, m.d, m.dff, slice1);
+                launch_skinny<T, 2, 1>(st, mt, grid, x, m.L, nullptr, 0, Wg, Wu, part1, m.d, m.dff, slice1);
             else
-                launch_skinny<T, T, 2, Ld<T>::vec>(st, mt, grid, x, m.L, Wg, Wu, part, m.d, m.dff, slice1);
-            const long n = (long)m.B * mt * m.dff;
-            hipLaunchKernelGGL(skinny_finish_gu_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part,
-                               act, ks1, m.B, mt, m.dff);
+                launch_skinny<T, 2, Ld<T>::vec>(st, mt, grid, x, m.L, nullptr, 0, Wg, Wu, part1, m.d, m.dff,
+                                                slice1);
         }
-        // phase 2: down projection
+        // phase 2: SwiGLU of the summed parts while staging, down projection, then the final sum
         {
             const dim3 grid((m.d + 64 * pl.vec2 - 1) / (64 * pl.vec2), ks2, m.B);
             if (pl.vec2 == 1)
-                launch_skinny<T, float, 1, 1>(st, mt, grid, act, mt, Wd, (const T *)nullptr, part, m.dff, m.d,
-                                              slice2);
+                launch_skinny<T, 1, 1>(st, mt, grid, (const T *)nullptr, 0, part1, ks1, Wd, (const T *)nullptr,
+                                       part2, m.dff, m.d, slice2);
             else
-                launch_skinny<T, float, 1, Ld<T>::vec>(st, mt, grid, act, mt, Wd, (const T *)nullptr, part,
-                                                       m.dff, m.d, slice2);
+                launch_skinny<T, 1, Ld<T>::vec>(st, mt, grid, (const T *)nullptr, 0, part1, ks1, Wd,
+                                                (const T *)nullptr, part2, m.dff, m.d, slice2);
             const long n = (long)m.B * mt * m.d;
             hipLaunchKernelGGL((skinny_finish_down_kernel<T>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                               st, part, Y, ks2, m.B, mt, m.d, (long)m.L, t0);
+                               st, part2, Y, ks2, m.B, mt, m.d, (long)m.L, t0);
         }
         if (hipGetLastError() != hipSuccess) return LORY_ERR_DEVICE;
     }
@@ -293,7 +284,7 @@ size_t dense_workspace_bytes(const Dims &m)
 {
     if (gemm_path(m)) return bf16_dense_workspace_bytes(m);
     const SkinnyPlan pl = (m.dtype == LORY_F32) ? skinny_plan<float>(m) : skinny_plan<__hip_bfloat16>(m);
-    return align_up(sizeof(float) * (pl.part + pl.act), 256);
+    return align_up(sizeof(float) * (pl.part1 + pl.part2), 256);
 }
 
 int dense_ffn_fwd(const Dims &m, const void *X, const void *Wbar, void *Y, void *ws, hipStream_t st)
