@@ -1,8 +1,10 @@
 // bf16 merged FFN forward and backward (paper Eq. 1 / Eq. 2, SwiGLU experts):
 // host-side orchestration of the MFMA kernels.
 //
-// The merged parameters of all segments (S * 3 * d * d_ff values) are never
-// held at once.  Each pass walks the expert matrices block by block; for a
+// Unless the caller asks for them (Wbar_save: the forward then merges straight
+// into the caller's buffer and the backward reads them there instead of
+// re-merging), the merged parameters of all segments (S * 3 * d * d_ff values)
+// are never held at once.  Each pass walks the expert matrices block by block; for a
 // block it (1) merges that block for ALL segments into a bounded slab (one read
 // of the expert stack, thin MFMA GEMM over the E experts), (2) runs the
 // per-segment token GEMMs that consume the slab.  The backward additionally

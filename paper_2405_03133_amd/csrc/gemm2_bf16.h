@@ -1,7 +1,7 @@
-// Second-generation batched bf16 MFMA GEMM for gfx950: 256 x 256 tiles fed by
-// a four-stage LDS ring that is filled with direct global->LDS loads
-// (global_load_lds_dwordx4), so that three K steps of operands are in flight
-// while one is being multiplied.  Same problem statement, operand layouts and
+// Persistent batched bf16 MFMA GEMM for gfx950: 256 x 256 tiles fed by a
+// four-stage LDS ring that is filled with direct global->LDS loads
+// (global_load_lds_dwordx4), so that two to three K steps of operands are in
+// flight while one is being multiplied.  Same problem statement, operand layouts and
 // epilogue interface as gemm_bf16.h (the dense contractions of the merged FFN,
 // paper Section 3.1 / Appendix B); this variant needs M % 256 == 0 and
 // N % (256 / NSET) == 0 and is used whenever the shape allows.
