@@ -192,7 +192,7 @@ int launch_route_bwd(const Dims &m, const void *R, const float *w, const float *
                      void *dX, float *dR, int accumulate, hipStream_t st)
 {
     // enough row blocks to give every CU a few workgroups, at least 8 rows each
-    int rb = (2048 + m.S - 1) / m.S;
+    int rb = (1024 + m.S - 1) / m.S;
     if (rb > m.T / 8) rb = m.T / 8;
     if (rb < 1) rb = 1;
     const int rows_per = (m.T + rb - 1) / rb;
