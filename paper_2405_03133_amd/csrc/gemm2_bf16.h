@@ -242,7 +242,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
                     for (int r = 0; r < 16; ++r) acc[s][i][j][r] = 0.f;
     };
 
-    for (int g = 0; g < kStages - 1; ++g) {
+    for (int g = 0; g < kStages; ++g) {  // the whole ring: K steps 0 .. 3
         const int gsrc = g < G ? g : G - 1;
         if (gsrc / total != ldA_tile) enter_tile_A(gsrc / total);
         if (gsrc / total != ldB_tile) enter_tile_B(gsrc / total);
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
     // g+3) and step g+1 has landed for everyone (its first slice can be fetched behind the
     // second slice's MFMAs).
     bf16x8 a0[MI], b0[NSET * NI], a1[MI], b1[NSET * NI];
-    wait_vmcnt<(kStages - 2) * 8>();  // steps 1 and 2 may still be in flight
+    wait_vmcnt<(kStages - 1) * 8>();  // steps 1 .. 3 may still be in flight
     ring_barrier();
 #pragma unroll
     for (int f = 0; f < 8; ++f) load_frag(smem, 0, f, a0, b0);
@@ -289,38 +289,40 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
     // about 16 cycles per load, so loads in adjacent slots (as when all eight sat in one half
     // step) stalled the waves for longer than the MFMAs they hide behind.  (Giving every wave
     // slots of its own was tried: the wave-dependent branches cost far more than they saved.)
-    //   first half:  A chunks of step g+2 (into the slot step g-2 left at the previous barrier)
-    //   second half: B chunks of step g+3 (into the slot step g-1 left at this step's barrier)
-    // The B operand is the one that streams from HBM, hence the longer lead.  Across a tile
-    // boundary the A chunks that the next tile's first step would issue are issued half a step
-    // early, in the last step of the tile (after_last), so that everything the next tile's first
-    // two steps wait for is older than the epilogue's stores: loads and stores share vmcnt and
+    //   first half:  A chunks of step g+3 (into the slot step g-1 left at the previous barrier)
+    //   second half: B chunks of step g+4 (into the slot step g itself left at this step's
+    //                barrier: every wave has fetched its last fragments of step g by then)
+    // so that, with the four ring slots, up to three and a half K steps of operands are in
+    // flight.  The B operand is the one that streams from HBM, hence the longer lead.  Across a
+    // tile boundary the A chunks that the next tile's first step would issue are issued half a
+    // step early, in the last step of the tile, so that everything the next tile's first three
+    // steps wait for is older than the epilogue's stores: loads and stores share vmcnt and
     // retire in order, and a wait may only leave younger operations pending.
     // Past the end of the stream the loads re-fetch the last K step into slots nobody reads, so
-    // "all but the newest 8 loads have landed" (vmcnt(8)) always means "step g+1 is complete".
+    // "all but the newest 16 loads have landed" (vmcnt(16)) always means "step g+1 is complete".
     // extra_now: store instructions of the previous tile's epilogue that may still be pending
-    // (only non-zero for the first two steps of a tile).
+    // (only non-zero for the first three steps of a tile).
     auto step = [&](int g, int extra_now, bool first_of_tile, bool last_of_tile) {
         const char *la = smem + (g & (kStages - 1)) * kStageBytes;
         const char *ln = smem + ((g + 1) & (kStages - 1)) * kStageBytes;
-        const int srcA = (g + 2 < G) ? (g + 2) : (G - 1);
+        const int srcA = (g + 3 < G) ? (g + 3) : (G - 1);
         if (!first_of_tile && srcA / total != ldA_tile) enter_tile_A(srcA / total);
 #pragma unroll
         for (int sl = 0; sl < 16; ++sl) {
             const int i = sl >> 2, q = sl & 3;
             acc[q / NI][i][q % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0[q], a0[i], acc[q / NI][i][q % NI], 0, 0, 0);
             if ((sl & 1) == 0) load_frag(la, 1, sl >> 1, a1, b1);
-            if (!first_of_tile && (sl & 3) == 1) issue_A(srcA, g + 2, sl >> 2);
+            if (!first_of_tile && (sl & 3) == 1) issue_A(srcA, g + 3, sl >> 2);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (extra_now == 32)
-            wait_vmcnt<40>();
+            wait_vmcnt<48>();
         else if (extra_now == 16)
-            wait_vmcnt<24>();
+            wait_vmcnt<32>();
         else
-            wait_vmcnt<8>();
+            wait_vmcnt<16>();
         ring_barrier();
-        const int srcB = (g + 3 < G) ? (g + 3) : (G - 1);  // K step to fetch
+        const int srcB = (g + 4 < G) ? (g + 4) : (G - 1);  // K step to fetch
         if (srcB / total != ldB_tile) enter_tile_B(srcB / total);
         if (last_of_tile && srcB / total != ldA_tile) enter_tile_A(srcB / total);
 #pragma unroll
@@ -328,8 +330,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
             const int i = sl >> 2, q = sl & 3;
             acc[q / NI][i][q % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1[q], a1[i], acc[q / NI][i][q % NI], 0, 0, 0);
             if ((sl & 1) == 0) load_frag(ln, 0, sl >> 1, a0, b0);
-            if ((sl & 3) == 1) issue_B(srcB, g + 3, sl >> 2);
-            if (last_of_tile && (sl & 3) == 3) issue_A(srcB, g + 3, sl >> 2);
+            if ((sl & 3) == 1) issue_B(srcB, g + 4, sl >> 2);
+            if (last_of_tile && (sl & 3) == 3) issue_A(srcB, g + 4, sl >> 2);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -391,8 +393,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
     int g = 0;
     for (int tile_i = 0; tile_i < my_tiles; ++tile_i) {
         zero_acc();
-        // the first two K steps of a tile run while the previous tile's stores drain
-        const int relaxed = (tile_i > 0) ? 2 : 0;
+        // the first three K steps of a tile run while the previous tile's stores drain
+        const int relaxed = (tile_i > 0) ? 3 : 0;
         for (int t = 0; t < total; ++t, ++g) step(g, t < relaxed ? extra : 0, t == 0, t == total - 1);
         epilogue(tile_i);
     }
