@@ -11,7 +11,7 @@ checked on sampled outputs that the fp64 oracle can compute one by one:
     layer (d_ff' = |J|) whose weight gradients, for the same dY, are the full
     layer's restricted to J;
   * an identity that holds at any size: sum_e w[s,e] dw[s,e] =
-    2 <Y_s, dY_s> + <G_s, dG_s>, evaluated from GPU outputs only.
+    2 <Y_s, dY_s> + <G_s, dG_s>, with the left side and <Y, dY> from GPU outputs.
 """
 import numpy as np
 import pytest
@@ -36,7 +36,7 @@ def host(t):
 
 
 @pytest.mark.timeout(1500)
-@pytest.mark.parametrize("name", ["C4", "C4_EP8", "C5_T64", "C5_T1024"])
+@pytest.mark.parametrize("name", ["C4", "C4_EP8", "C5_T64", "C5_T128", "C5_T1024", "P15_E8"])
 def test_full_size_sampled(name):
     cfg = CONFIGS[name]
     print(f"[full] generating {cfg}", flush=True)
@@ -96,7 +96,11 @@ def test_full_size_sampled(name):
         dA = dYs[s].astype(np.float64) @ md.T
         dG = dA * f["U"] * sg * (1.0 + f["G"] * (1.0 - sg))
         rhs = 2.0 * yy[s] + float(np.sum(f["G"] * dG))
-        assert abs(lhs[s] - rhs) <= 2e-2 * abs(rhs) + 1e-6, (s, lhs[s], rhs)
+        # both sides are sums of products that largely cancel, so the bound is relative to the
+        # size of the terms (Cauchy-Schwarz), at the bf16 tolerance of the tensors involved
+        scale = (2.0 * np.linalg.norm(f["Y"]) * np.linalg.norm(dYs[s].astype(np.float64))
+                 + np.linalg.norm(f["G"]) * np.linalg.norm(dG))
+        assert abs(lhs[s] - rhs) <= TOL * scale, (s, lhs[s], rhs, scale)
         del f, g, md, dA, dG, sg
 
     # ---- sampled d_ff blocks: weight gradients and saved activations
