@@ -162,20 +162,25 @@ int lory_route_bwd(const lory_shape *shape, const void *R, const float *w, const
  * inference"; Appendix G.1): one routing decision per sequence and layer from
  * the mean hidden state of the whole prompt, and the merged FFN it selects,
  * materialised once and then used like a dense FFN for the whole generation.
- *   w[b,:]   = softmax(mean over the L prompt tokens of X_prompt[b] . R)
+ *   w[b,:]   = softmax(mean over the prompt tokens of X_prompt[b] . R)
  *   Wx_bar_b = sum_e w[b,e] Wx[e]      x in {gate, up, down}
- * shape: L = prompt length (any length > 0, the same for all B sequences) and
- *        T = L (one segment per sequence; anything else is LORY_ERR_SHAPE);
+ * shape: L = rows per sequence of X_prompt (any length > 0) and T = L (one
+ *        segment per sequence; anything else is LORY_ERR_SHAPE);
  *        LORY_BF16 needs d % 64 == 0 and d_ff % 64 == 0 only.
- * in:  X_prompt [B, L, d], R [d, E], Wg, Wu [E, d, d_ff], Wd [E, d_ff, d] (dtype)
+ * in:  X_prompt [B, L, d], R [d, E], Wg, Wu [E, d, d_ff], Wd [E, d_ff, d] (dtype);
+ *      prompt_len_opt: NULL (every prompt has L tokens) or B int32 on the
+ *      device, 4-byte aligned: sequence b's prompt is the first prompt_len[b]
+ *      rows of X_prompt[b], the rest is padding that is never read (the mean
+ *      is what lets the router take prompts of different lengths); values
+ *      are clamped to 1 .. L
  * out: w [B, E] fp32; Wbar: 3 * B * d * d_ff elements of dtype, laid out
  *      [Wg_bar | Wu_bar | Wd_bar], each [B, rows, cols] like one expert matrix
  *      (the layout of Wbar_save).  Needs no workspace.
  * Per-segment routing at inference, the other mode the paper evaluates, is
  * lory_route + lory_merged_ffn_fwd as in training.
  */
-int lory_prompt_merge(const lory_shape *shape, const void *X_prompt, const void *R,
-                      const void *Wg, const void *Wu, const void *Wd,
+int lory_prompt_merge(const lory_shape *shape, const void *X_prompt, const int32_t *prompt_len_opt,
+                      const void *R, const void *Wg, const void *Wu, const void *Wd,
                       float *w, void *Wbar, void *stream);
 
 /*

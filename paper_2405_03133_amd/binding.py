@@ -75,7 +75,7 @@ def lib() -> ctypes.CDLL:
         L.lory_route.restype = ci
         L.lory_route_bwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, ci, vp]
         L.lory_route_bwd.restype = ci
-        L.lory_prompt_merge.argtypes = [sp] + [vp] * 8
+        L.lory_prompt_merge.argtypes = [sp] + [vp] * 9
         L.lory_prompt_merge.restype = ci
         L.lory_dense_ffn_fwd.argtypes = [sp, vp, vp, vp, vp, sz, vp]
         L.lory_dense_ffn_fwd.restype = ci
@@ -218,8 +218,9 @@ def lory_route_bwd(R: torch.Tensor, w: torch.Tensor, hbar: torch.Tensor, dw: tor
 
 def lory_prompt_merge(X_prompt: torch.Tensor, R: torch.Tensor, Wg: torch.Tensor, Wu: torch.Tensor,
                       Wd: torch.Tensor, w: Optional[torch.Tensor] = None,
-                      Wbar: Optional[torch.Tensor] = None):
-    """Prompt-only routing: (w [B,E] fp32, Wbar [3, B, d*d_ff] of X's dtype) from the whole prompt."""
+                      Wbar: Optional[torch.Tensor] = None, prompt_len: Optional[torch.Tensor] = None):
+    """Prompt-only routing: (w [B,E] fp32, Wbar [3, B, d*d_ff] of X's dtype) from the whole prompt;
+    prompt_len [B] int32 gives the true lengths of prompts padded to X_prompt's L rows."""
     B, L, d = X_prompt.shape
     E, _, d_ff = Wg.shape
     if tuple(Wu.shape) != (E, d, d_ff) or tuple(Wd.shape) != (E, d_ff, d) or tuple(R.shape) != (d, E):
@@ -236,7 +237,9 @@ def lory_prompt_merge(X_prompt: torch.Tensor, R: torch.Tensor, Wg: torch.Tensor,
         raise ValueError("w must be fp32 [B, E]")
     if Wbar.dtype != X_prompt.dtype or Wbar.numel() != 3 * B * d * d_ff:
         raise ValueError("Wbar must hold 3*B*d*d_ff elements of X's dtype")
-    _check(lib().lory_prompt_merge(ctypes.byref(shape), _ptr(X_prompt), _ptr(R), _ptr(Wg), _ptr(Wu), _ptr(Wd),
+    if prompt_len is not None and (prompt_len.dtype != torch.int32 or tuple(prompt_len.shape) != (B,)):
+        raise ValueError("prompt_len must be int32 [B]")
+    _check(lib().lory_prompt_merge(ctypes.byref(shape), _ptr(X_prompt), _ptr(prompt_len), _ptr(R), _ptr(Wg), _ptr(Wu), _ptr(Wd),
                                    _ptr(w), _ptr(Wbar), _stream()), "lory_prompt_merge")
     return w, Wbar
 

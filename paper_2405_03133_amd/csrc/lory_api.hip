@@ -109,7 +109,7 @@ int lory_route(const lory_shape *shape, const void *X, const void *R, float *w, 
     const double esz = (m.dtype == LORY_F32) ? 4.0 : 2.0;
     lory::prof::Range r((hipStream_t)stream, lory::prof::kRoute, 2.0 * m.S * m.d * m.E + (double)m.tokens * m.d,
                         esz * ((double)m.tokens * m.d + (double)m.d * m.E) + 4.0 * m.S * m.E);
-    return lory::route_launch(m, X, R, w, hbar_opt, (hipStream_t)stream);
+    return lory::route_launch(m, X, R, w, hbar_opt, nullptr, (hipStream_t)stream);
 }
 
 int lory_route_bwd(const lory_shape *shape, const void *R, const float *w, const float *hbar,
@@ -132,12 +132,14 @@ int lory_route_bwd(const lory_shape *shape, const void *R, const float *w, const
     return lory::route_bwd_launch(m, R, w, hbar, dw, dX, dR, accumulate_dR, (hipStream_t)stream);
 }
 
-int lory_prompt_merge(const lory_shape *shape, const void *X_prompt, const void *R, const void *Wg,
-                      const void *Wu, const void *Wd, float *w, void *Wbar, void *stream)
+int lory_prompt_merge(const lory_shape *shape, const void *X_prompt, const int32_t *prompt_len_opt,
+                      const void *R, const void *Wg, const void *Wu, const void *Wd, float *w, void *Wbar,
+                      void *stream)
 {
     const int rc = check_shape_infer(shape);
     if (rc != LORY_OK) return rc;
     if (!X_prompt || !R || !Wg || !Wu || !Wd || !w || !Wbar) return LORY_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(prompt_len_opt) & 3u) != 0) return LORY_ERR_ALIGN;
     if (!aligned16(X_prompt) || !aligned16(R) || !aligned16(Wg) || !aligned16(Wu) || !aligned16(Wd) ||
         !aligned16(w) || !aligned16(Wbar))
         return LORY_ERR_ALIGN;
@@ -147,7 +149,7 @@ int lory_prompt_merge(const lory_shape *shape, const void *X_prompt, const void 
         const double esz = (m.dtype == LORY_F32) ? 4.0 : 2.0;
         lory::prof::Range r(st, lory::prof::kRoute, 2.0 * m.S * m.d * m.E + (double)m.tokens * m.d,
                             esz * ((double)m.tokens * m.d + (double)m.d * m.E) + 4.0 * m.S * m.E);
-        const int rr = lory::route_launch(m, X_prompt, R, w, nullptr, st);
+        const int rr = lory::route_launch(m, X_prompt, R, w, nullptr, prompt_len_opt, st);
         if (rr != LORY_OK) return rr;
     }
     if (m.dtype == LORY_F32)

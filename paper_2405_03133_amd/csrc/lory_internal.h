@@ -61,7 +61,8 @@ private:
 }  // namespace prof
 
 // ---- routing (route.hip)
-int route_launch(const Dims &m, const void *X, const void *R, float *w, float *hbar, hipStream_t st);
+int route_launch(const Dims &m, const void *X, const void *R, float *w, float *hbar, const int32_t *seg_len,
+                 hipStream_t st);
 
 // ---- routing backward (route_bwd.hip)
 int route_bwd_launch(const Dims &m, const void *R, const float *w, const float *hbar, const float *dw,

@@ -53,6 +53,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restric
                                                               const T *__restrict__ R,
                                                               float *__restrict__ w,
                                                               float *__restrict__ hbar_out,
+                                                              const int32_t *__restrict__ seg_len,
                                                               int Tseg, int d, int E, int N)
 {
     constexpr int VEC = VECTOR ? Vec<T>::n : 1;
@@ -67,7 +68,14 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restric
     const int tx = tid % kColThreads;
     const int ty = tid / kColThreads;
     const T *Xs = X + (size_t)s * Tseg * d;
-    const float invT = 1.0f / (float)Tseg;
+    // rows that enter the mean: all Tseg, or (prompts of different lengths, padded to Tseg rows)
+    // the first seg_len[s] of them, clamped to 1 .. Tseg
+    int rows = Tseg;
+    if (seg_len) {
+        rows = seg_len[s];
+        rows = rows < 1 ? 1 : (rows > Tseg ? Tseg : rows);
+    }
+    const float invT = 1.0f / (float)rows;
 
     // ---- segment mean, a chunk of kColThreads*VEC columns at a time
     for (int c0 = 0; c0 < d; c0 += kColThreads * VEC) {
@@ -76,7 +84,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restric
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
         if (c < d) {
-            for (int t = ty; t < Tseg; t += kRowGroups) {
+            for (int t = ty; t < rows; t += kRowGroups) {
                 float v[VEC];
                 if constexpr (VECTOR) {
                     Vec<T>::load(Xs + (size_t)t * d + c, v);
@@ -146,7 +154,8 @@ size_t route_lds_bytes(int d, int vec)
 }
 
 template <typename T, bool VECTOR>
-int launch_route(const Dims &m, const void *X, const void *R, float *w, float *hbar, hipStream_t st)
+int launch_route(const Dims &m, const void *X, const void *R, float *w, float *hbar, const int32_t *seg_len,
+                 hipStream_t st)
 {
     const size_t lds = route_lds_bytes(m.d, VECTOR ? Vec<T>::n : 1);
     if (lds > 48 * 1024) {
@@ -155,21 +164,22 @@ int launch_route(const Dims &m, const void *X, const void *R, float *w, float *h
             return LORY_ERR_DEVICE;
     }
     hipLaunchKernelGGL((route_kernel<T, VECTOR>), dim3(m.S), dim3(kRouteThreads), lds, st,
-                       (const T *)X, (const T *)R, w, hbar, m.T, m.d, m.E, m.N);
+                       (const T *)X, (const T *)R, w, hbar, seg_len, m.T, m.d, m.E, m.N);
     return launch_status();
 }
 
 }  // namespace
 
-int route_launch(const Dims &m, const void *X, const void *R, float *w, float *hbar, hipStream_t st)
+int route_launch(const Dims &m, const void *X, const void *R, float *w, float *hbar, const int32_t *seg_len,
+                 hipStream_t st)
 {
     static_assert(kMaxE == 64, "logit stage assumes E <= 64");
     if (m.dtype == LORY_F32) {
-        if (m.d % Vec<float>::n == 0) return launch_route<float, true>(m, X, R, w, hbar, st);
-        return launch_route<float, false>(m, X, R, w, hbar, st);
+        if (m.d % Vec<float>::n == 0) return launch_route<float, true>(m, X, R, w, hbar, seg_len, st);
+        return launch_route<float, false>(m, X, R, w, hbar, seg_len, st);
     }
-    if (m.d % Vec<__hip_bfloat16>::n == 0) return launch_route<__hip_bfloat16, true>(m, X, R, w, hbar, st);
-    return launch_route<__hip_bfloat16, false>(m, X, R, w, hbar, st);
+    if (m.d % Vec<__hip_bfloat16>::n == 0) return launch_route<__hip_bfloat16, true>(m, X, R, w, hbar, seg_len, st);
+    return launch_route<__hip_bfloat16, false>(m, X, R, w, hbar, seg_len, st);
 }
 
 }  // namespace lory

@@ -92,14 +92,19 @@ def test_inference_entry_points_validation():
     out = ctypes.c_size_t(5)
     assert L.lory_workspace_bytes(bad, lb.LORY_PASS_DENSE, ctypes.byref(out)) == lb.LORY_ERR_SHAPE
     assert out.value == 5
-    assert L.lory_prompt_merge(bad, F, F, F, F, F, F, F, None) == lb.LORY_ERR_SHAPE
+    assert L.lory_prompt_merge(bad, F, None, F, F, F, F, F, F, None) == lb.LORY_ERR_SHAPE
     assert L.lory_dense_ffn_fwd(bad, F, F, F, F, need, None) == lb.LORY_ERR_SHAPE
-    for i in range(7):
-        args = [F] * 7
+    for i in range(8):
+        if i == 1:
+            continue                           # prompt_len_opt may be NULL
+        args = [F] * 8
         args[i] = None
         assert L.lory_prompt_merge(sp, *args, None) == lb.LORY_ERR_NULL
         args[i] = F + 8
         assert L.lory_prompt_merge(sp, *args, None) == lb.LORY_ERR_ALIGN
+    args = [F] * 8
+    args[1] = F + 2                            # lengths need 4-byte alignment only
+    assert L.lory_prompt_merge(sp, *args, None) == lb.LORY_ERR_ALIGN
     for i in range(4):
         args = [F] * 4
         args[i] = None

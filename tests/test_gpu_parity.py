@@ -480,3 +480,26 @@ def test_autograd_wrapper_matches_oracle_layer_gradient(cfg):
     compare(cfg, got, ref, ("Y", "dX", "dWg", "dWu", "dWd"), tol)
     # dR inherits the rounding of dw through a cancelling sum (and bf16 storage of the gradient)
     compare(cfg, got, ref, ("dR",), 1e-3 if cfg.dtype == "f32" else 3e-2)
+
+
+def test_prompt_merge_with_prompts_of_different_lengths():
+    """Padded prompts with a length per sequence: routing on the mean of the first len[b] rows only
+    (the oracle routes each sequence on its own, with T = L = len[b]); padding rows hold NaN."""
+    cfg = LoryConfig("inf_ragged", B=4, L=96, T=96, d=128, d_ff=192, E=8, dtype="bf16", seed=57)
+    t = make_inputs(cfg, structured=True, with_dy=False)
+    lens = np.array([96, 1, 37, 64], dtype=np.int32)
+    Xp = t["X"].copy()
+    for b, n in enumerate(lens):
+        Xp[b, n:] = np.nan
+    X, R = to_dev(Xp, cfg), to_dev(t["R"], cfg)
+    Wg, Wu, Wd = (to_dev(t[k], cfg) for k in ("Wg", "Wu", "Wd"))
+    w, Wbar = lb.lory_prompt_merge(X, R, Wg, Wu, Wd, prompt_len=torch.from_numpy(lens).cuda())
+    torch.cuda.synchronize()
+    got_w = host(w)
+    assert np.isfinite(got_w).all() and torch.isfinite(Wbar.float()).all()
+    for b, n in enumerate(lens):
+        ref = orc.route(t["X"][b:b + 1, :n], t["R"], int(n))["w"][0]
+        assert rel_l2(got_w[b], ref) <= 1e-5, (b, n)
+    D = cfg.d * cfg.d_ff
+    ref_g = np.einsum("be,en->bn", got_w, t["Wg"].astype(np.float64).reshape(cfg.E, D))
+    assert rel_l2(host(Wbar).reshape(3, cfg.B, D)[0], ref_g) <= 4e-3
