@@ -49,6 +49,8 @@ def parse_args():
                     help="do not hand the forward's merged parameters to the backward (it re-merges)")
     ap.add_argument("--slab-mb", type=int, default=0)
     ap.add_argument("--verbose", action="store_true")
+    ap.add_argument("--fwd-only", action="store_true",
+                    help="time lory_route + lory_merged_ffn_fwd only (the forward configurations of the sweep)")
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph of the step instead of launching every step eagerly "
                          "(measured equal: the host stays ahead of the GPU either way)")
@@ -191,10 +193,10 @@ def main():
     w = torch.empty((cfg.S, cfg.E), dtype=torch.float32, device=dev)
     Y = torch.empty_like(X)
     G = U = None
-    if not args.no_save:
+    if not args.no_save and not args.fwd_only:
         G = torch.empty((cfg.tokens, cfg.d_ff), dtype=dt, device=dev)
         U = torch.empty_like(G)
-    Wbar = None if args.no_merged_save else lb.alloc_merged_save(shape)
+    Wbar = None if (args.no_merged_save or args.fwd_only) else lb.alloc_merged_save(shape)
     dX = torch.empty_like(X)
     dWg = torch.empty(Wg.shape, dtype=gdt, device=dev)
     dWu = torch.empty(Wu.shape, dtype=gdt, device=dev)
@@ -206,6 +208,8 @@ def main():
     def step():
         lb.lory_route(X, R, cfg.T, w=w, hbar=hbar, d_ff=cfg.d_ff)
         lb.lory_merged_ffn_fwd(X, w, Wg, Wu, Wd, cfg.T, Y=Y, G_save=G, U_save=U, workspace=ws_f, Wbar_save=Wbar)
+        if args.fwd_only:
+            return
         lb.lory_merged_ffn_bwd(X, w, Wg, Wu, Wd, dY, cfg.T, G_save=G, U_save=U, dX=dX, dWg=dWg, dWu=dWu,
                                dWd=dWd, dw=dw, grad_dtype=gdt, workspace=ws_b, Wbar_save=Wbar)
         lb.lory_route_bwd(R, w, hbar, dw, dX, cfg.T, dR=dR, d_ff=cfg.d_ff)
@@ -271,7 +275,8 @@ def main():
             roofline = {"kernel": dominant, "bound": "hbm", "achieved": kd["gbs"], "peak": PEAK_HBM_GBS,
                         "unit": "GB/s", "frac": kd["gbs"] / PEAK_HBM_GBS}
         roofline["avg_launch_us"] = kd["avg_us"]
-        default_launch = not (args.no_save or args.no_merged_save or args.slab_mb or args.grad_dtype != "bf16")
+        default_launch = not (args.no_save or args.no_merged_save or args.slab_mb or args.grad_dtype != "bf16"
+                              or args.fwd_only)
         roofline["traffic"] = TRAFFIC_BYTES.get((args.config, dominant)) if default_launch else None
 
     # The paper's utilisation analysis (appendix on expert utilisation) calls an expert activated for
@@ -279,8 +284,9 @@ def main():
     # weights give nearly uniform routing.
     routing = {"experts_with_w_above_2_over_E": int((w > 2.0 / cfg.E).any(dim=0).sum().item()),
                "mean_max_w": float(w.max(dim=1).values.mean().item())}
-    gemm_tflops = cfg.gemm_flops(True) / (ms_per_step * 1e-3) / 1e12
-    all_tflops = (cfg.gemm_flops(True) + cfg.merge_flops(4)) / (ms_per_step * 1e-3) / 1e12
+    with_bwd = not args.fwd_only
+    gemm_tflops = cfg.gemm_flops(with_bwd) / (ms_per_step * 1e-3) / 1e12
+    all_tflops = (cfg.gemm_flops(with_bwd) + cfg.merge_flops(4 if with_bwd else 1)) / (ms_per_step * 1e-3) / 1e12
     out = {
         "metric": "merged-MoE-FFN tokens/sec/GPU (fwd+bwd) + % bf16 MFMA peak",
         "value": tokens_per_s,
@@ -295,7 +301,7 @@ def main():
         "dtype": cfg.dtype,
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} L={cfg.L} T={cfg.T} d={cfg.d} d_ff={cfg.d_ff} E={cfg.E} "
-                               f"{cfg.dtype} route+fwd+bwd+route_bwd, grad_dtype={args.grad_dtype}, "
+                               f"{cfg.dtype} {'route+fwd' if args.fwd_only else 'route+fwd+bwd+route_bwd'}, grad_dtype={args.grad_dtype}, "
                                f"save_GU={not args.no_save}, save_merged={Wbar is not None}, "
                                f"hip_graph={args.graph}",
                    "tokens": cfg.tokens, "segments": cfg.S},
