@@ -165,7 +165,10 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const TW *__restrict
         }
 }
 
-// Y[b][t0 + t][j] = sum over the K splits.   part: [ks][B][1][mt][N]
+// Y[b][t0 + t][j] = sum over the K splits, in split order.   part: [ks][B][1][mt][N]
+// One wavefront-wide group of 8 lanes per output element would change the order; instead every
+// thread keeps its element and fetches eight parts at a time, so the loads overlap and the adds
+// stay sequential.
 template <typename T>
 __global__ void skinny_finish_down_kernel(const float *__restrict__ part, T *__restrict__ Y, int ksplit, int B,
                                           int mt, int N, long y_rows, int t0)
@@ -176,8 +179,18 @@ __global__ void skinny_finish_down_kernel(const float *__restrict__ part, T *__r
     const int n = (int)(i % N);
     const int t = (int)((i / N) % mt);
     const int b = (int)(i / ((long)N * mt));
+    const float *src = part + ((size_t)b * mt + t) * N + n;
+    const size_t pitch = (size_t)B * mt * N;
     float y = 0.f;
-    for (int ks = 0; ks < ksplit; ++ks) y += part[(((size_t)ks * B + b) * mt + t) * N + n];
+    int ks = 0;
+    for (; ks + 8 <= ksplit; ks += 8) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = src[(size_t)(ks + j) * pitch];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) y += v[j];
+    }
+    for (; ks < ksplit; ++ks) y += src[(size_t)ks * pitch];
     Ld<T>::store(Y + ((size_t)b * y_rows + t0 + t) * N + n, y);
 }
 

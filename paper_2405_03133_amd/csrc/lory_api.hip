@@ -149,7 +149,12 @@ int lory_prompt_merge(const lory_shape *shape, const void *X_prompt, const int32
         const double esz = (m.dtype == LORY_F32) ? 4.0 : 2.0;
         lory::prof::Range r(st, lory::prof::kRoute, 2.0 * m.S * m.d * m.E + (double)m.tokens * m.d,
                             esz * ((double)m.tokens * m.d + (double)m.d * m.E) + 4.0 * m.S * m.E);
-        const int rr = lory::route_launch(m, X_prompt, R, w, nullptr, prompt_len_opt, st);
+        // Long prompts of a few sequences: the mean is taken in two stages over many workgroups,
+        // with the partial sums parked in Wbar, which the merges overwrite afterwards.
+        const size_t esize = (m.dtype == LORY_F32) ? 4 : 2;
+        const bool two_stage = m.L >= 256 && lory::prompt_route_scratch_bytes(m) <= (size_t)3 * m.B * m.D * esize;
+        const int rr = two_stage ? lory::prompt_route_launch(m, X_prompt, prompt_len_opt, R, w, (float *)Wbar, st)
+                                 : lory::route_launch(m, X_prompt, R, w, nullptr, prompt_len_opt, st);
         if (rr != LORY_OK) return rr;
     }
     if (m.dtype == LORY_F32)

@@ -64,6 +64,10 @@ private:
 int route_launch(const Dims &m, const void *X, const void *R, float *w, float *hbar, const int32_t *seg_len,
                  hipStream_t st);
 
+size_t prompt_route_scratch_bytes(const Dims &m);
+int prompt_route_launch(const Dims &m, const void *X, const int32_t *len, const void *R, float *w, float *scratch,
+                        hipStream_t st);
+
 // ---- routing backward (route_bwd.hip)
 int route_bwd_launch(const Dims &m, const void *R, const float *w, const float *hbar, const float *dw,
                      void *dX, float *dR, int accumulate, hipStream_t st);

@@ -148,6 +148,133 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restric
     }
 }
 
+// ---- routing on the mean of a whole (long) prompt, two stages so that a handful of sequences
+// still fills the chip.  Stage 1: grid (sequences, row chunks), column sums of the chunk's rows
+// (only rows below the sequence's prompt length) into part[b][chunk][d].  Stage 2: one workgroup
+// per sequence adds the chunks in order, divides by the length, and runs the logits and the
+// softmax exactly like route_kernel.
+constexpr int kPromptChunkRows = 64;
+
+template <typename T>
+__global__ __launch_bounds__(256) void prompt_sum_kernel(const T *__restrict__ X, const int32_t *__restrict__ len,
+                                                         float *__restrict__ part, int L, int d, int chunks)
+{
+    constexpr int VEC = Vec<T>::n;
+    const int b = blockIdx.x, ch = blockIdx.y;
+    int rows = len ? len[b] : L;
+    rows = rows < 1 ? 1 : (rows > L ? L : rows);
+    const int r0 = ch * kPromptChunkRows;
+    const int r1 = (r0 + kPromptChunkRows < rows) ? (r0 + kPromptChunkRows) : rows;
+    const T *Xb = X + (size_t)b * L * d;
+    float *dst = part + ((size_t)b * chunks + ch) * d;
+    if (d % VEC == 0) {
+        for (int c = threadIdx.x * VEC; c < d; c += 256 * VEC) {
+            float acc[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+            for (int t = r0; t < r1; ++t) {
+                float v[VEC];
+                Vec<T>::load(Xb + (size_t)t * d + c, v);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] += v[i];
+            }
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) dst[c + i] = acc[i];
+        }
+    } else {
+        for (int c = threadIdx.x; c < d; c += 256) {
+            float acc = 0.f;
+            for (int t = r0; t < r1; ++t) acc += Vec<T>::one(Xb + (size_t)t * d + c);
+            dst[c] = acc;
+        }
+    }
+}
+
+// grid = sequences, block = 1024, dynamic LDS = (d + 16 * 64) floats.
+template <typename T>
+__global__ __launch_bounds__(kRouteThreads) void prompt_finish_kernel(const float *__restrict__ part,
+                                                                      const int32_t *__restrict__ len,
+                                                                      const T *__restrict__ R,
+                                                                      float *__restrict__ w, int L, int d, int E,
+                                                                      int chunks)
+{
+    extern __shared__ float lds[];
+    float *hbar = lds;         // [d]
+    float *zpart = lds + d;    // [16][64]
+    const int b = blockIdx.x, tid = threadIdx.x;
+    int rows = len ? len[b] : L;
+    rows = rows < 1 ? 1 : (rows > L ? L : rows);
+    const int used = (rows + kPromptChunkRows - 1) / kPromptChunkRows;
+    const float inv = 1.0f / (float)rows;
+    for (int c = tid; c < d; c += kRouteThreads) {
+        const float *src = part + (size_t)b * chunks * d + c;
+        float sum = 0.f;
+        int ch = 0;
+        for (; ch + 8 <= used; ch += 8) {  // loads overlap, adds stay in chunk order
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = src[(size_t)(ch + i) * d];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sum += v[i];
+        }
+        for (; ch < used; ++ch) sum += src[(size_t)ch * d];
+        hbar[c] = sum * inv;
+    }
+    __syncthreads();
+    {
+        const int e = tid % 64, jg = tid / 64;
+        float acc = 0.f;
+        if (e < E) {
+            int j = jg;
+            for (; j + 7 * 16 < d; j += 8 * 16) {
+                float r[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) r[i] = Vec<T>::one(R + (size_t)(j + 16 * i) * E + e);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc += hbar[j + 16 * i] * r[i];
+            }
+            for (; j < d; j += 16) acc += hbar[j] * Vec<T>::one(R + (size_t)j * E + e);
+        }
+        zpart[jg * 64 + e] = acc;
+    }
+    __syncthreads();
+    if (tid < 64) {
+        float z = -INFINITY;
+        if (tid < E) {
+            z = 0.f;
+#pragma unroll
+            for (int g = 0; g < 16; ++g) z += zpart[g * 64 + tid];
+        }
+        float zmax = z;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, off, 64));
+        const float pexp = (tid < E) ? expf(z - zmax) : 0.f;
+        float denom = pexp;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) denom += __shfl_xor(denom, off, 64);
+        if (tid < E) w[(size_t)b * E + tid] = pexp / denom;
+    }
+}
+
+template <typename T>
+int launch_prompt_route(const Dims &m, const void *X, const int32_t *len, const void *R, float *w, float *scratch,
+                        hipStream_t st)
+{
+    const int chunks = (m.L + kPromptChunkRows - 1) / kPromptChunkRows;
+    hipLaunchKernelGGL((prompt_sum_kernel<T>), dim3(m.B, chunks), dim3(256), 0, st, (const T *)X, len, scratch, m.L,
+                       m.d, chunks);
+    if (hipGetLastError() != hipSuccess) return LORY_ERR_DEVICE;
+    const size_t lds = sizeof(float) * ((size_t)m.d + 16 * 64);
+    if (lds > 48 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&prompt_finish_kernel<T>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return LORY_ERR_DEVICE;
+    }
+    hipLaunchKernelGGL((prompt_finish_kernel<T>), dim3(m.B), dim3(kRouteThreads), lds, st, scratch, len,
+                       (const T *)R, w, m.L, m.d, m.E, chunks);
+    return launch_status();
+}
+
 size_t route_lds_bytes(int d, int vec)
 {
     return sizeof(float) * ((size_t)d + (size_t)kRowGroups * kColThreads * vec + 16 * 64);
@@ -169,6 +296,21 @@ int launch_route(const Dims &m, const void *X, const void *R, float *w, float *h
 }
 
 }  // namespace
+
+size_t prompt_route_scratch_bytes(const Dims &m)
+{
+    const size_t chunks = ((size_t)m.L + kPromptChunkRows - 1) / kPromptChunkRows;
+    return sizeof(float) * (size_t)m.B * chunks * m.d;
+}
+
+// Routing weights of every sequence from the mean of its whole prompt (m.T == m.L).  `scratch`
+// holds prompt_route_scratch_bytes(m) bytes.
+int prompt_route_launch(const Dims &m, const void *X, const int32_t *len, const void *R, float *w, float *scratch,
+                        hipStream_t st)
+{
+    if (m.dtype == LORY_F32) return launch_prompt_route<float>(m, X, len, R, w, scratch, st);
+    return launch_prompt_route<__hip_bfloat16>(m, X, len, R, w, scratch, st);
+}
 
 int route_launch(const Dims &m, const void *X, const void *R, float *w, float *hbar, const int32_t *seg_len,
                  hipStream_t st)

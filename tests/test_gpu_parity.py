@@ -336,6 +336,9 @@ INFER_CASES = [
      (1, 2, 8, 11, 64, 192)),
     (LoryConfig("inf_bf16_wide", B=2, L=96, T=96, d=1024, d_ff=2816, E=32, dtype="bf16", seed=54), 96,
      (1, 5, 256)),
+    # prompts long enough for the two-stage mean (vector and scalar column paths)
+    (LoryConfig("inf_bf16_long", B=3, L=1000, T=1000, d=256, d_ff=320, E=16, dtype="bf16", seed=58), 1000, (1, 4)),
+    (LoryConfig("inf_f32_long_odd", B=2, L=300, T=300, d=50, d_ff=36, E=3, dtype="f32", seed=59), 300, (2,)),
 ]
 
 
@@ -486,12 +489,13 @@ def test_autograd_wrapper_matches_oracle_layer_gradient(cfg):
     compare(cfg, got, ref, ("dR",), 1e-3 if cfg.dtype == "f32" else 3e-2)
 
 
-def test_prompt_merge_with_prompts_of_different_lengths():
+@pytest.mark.parametrize("L,lens", [(96, [96, 1, 37, 64]), (512, [512, 1, 300, 257])], ids=["short", "long"])
+def test_prompt_merge_with_prompts_of_different_lengths(L, lens):
     """Padded prompts with a length per sequence: routing on the mean of the first len[b] rows only
     (the oracle routes each sequence on its own, with T = L = len[b]); padding rows hold NaN."""
-    cfg = LoryConfig("inf_ragged", B=4, L=96, T=96, d=128, d_ff=192, E=8, dtype="bf16", seed=57)
+    cfg = LoryConfig("inf_ragged", B=4, L=L, T=L, d=128, d_ff=192, E=8, dtype="bf16", seed=57)
     t = make_inputs(cfg, structured=True, with_dy=False)
-    lens = np.array([96, 1, 37, 64], dtype=np.int32)
+    lens = np.array(lens, dtype=np.int32)
     Xp = t["X"].copy()
     for b, n in enumerate(lens):
         Xp[b, n:] = np.nan
