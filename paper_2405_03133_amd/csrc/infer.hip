@@ -98,11 +98,26 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const TW *__restrict
         if constexpr (NMAT == 2) {
             xs[t * kMaxSlice + k] = to_f32(x[((size_t)b * x_rows + t) * K + k0 + k]);
         } else {
+            const float *pg = gu + ((size_t)b * 2 * MT + t) * K + k0 + k;   // split 0, gate
+            const size_t pitch = (size_t)B * 2 * MT * K, up = (size_t)MT * K;
             float g = 0.f, u = 0.f;
-            for (int ks = 0; ks < gu_ks; ++ks) {
-                const float *pp = gu + (((size_t)ks * B + b) * 2) * MT * K + k0 + k;
-                g += pp[(size_t)t * K];
-                u += pp[((size_t)MT + t) * K];
+            int ks = 0;
+            for (; ks + 4 <= gu_ks; ks += 4) {  // loads overlap, adds stay in split order
+                float vg[4], vu[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    vg[j] = pg[(size_t)(ks + j) * pitch];
+                    vu[j] = pg[(size_t)(ks + j) * pitch + up];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    g += vg[j];
+                    u += vu[j];
+                }
+            }
+            for (; ks < gu_ks; ++ks) {
+                g += pg[(size_t)ks * pitch];
+                u += pg[(size_t)ks * pitch + up];
             }
             xs[t * kMaxSlice + k] = g / (1.0f + expf(-g)) * u;
         }
