@@ -84,7 +84,23 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restric
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
         if (c < d) {
-            for (int t = ty; t < rows; t += kRowGroups) {
+            int t = ty;
+            for (; t + 3 * kRowGroups < rows; t += 4 * kRowGroups) {  // four rows in flight, added in row order
+                float v[4][VEC];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if constexpr (VECTOR) {
+                        Vec<T>::load(Xs + (size_t)(t + u * kRowGroups) * d + c, v[u]);
+                    } else {
+                        v[u][0] = Vec<T>::one(Xs + (size_t)(t + u * kRowGroups) * d + c);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc[i] += v[u][i];
+            }
+            for (; t < rows; t += kRowGroups) {
                 float v[VEC];
                 if constexpr (VECTOR) {
                     Vec<T>::load(Xs + (size_t)t * d + c, v);
@@ -118,7 +134,15 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restric
         const int jg = tid / 64;
         float acc = 0.f;
         if (e < E) {
-            for (int j = jg; j < d; j += 16) acc += hbar[j] * Vec<T>::one(R + (size_t)j * E + e);
+            int j = jg;
+            for (; j + 7 * 16 < d; j += 8 * 16) {  // eight loads in flight, added in order
+                float r[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) r[i] = Vec<T>::one(R + (size_t)(j + 16 * i) * E + e);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc += hbar[j + 16 * i] * r[i];
+            }
+            for (; j < d; j += 16) acc += hbar[j] * Vec<T>::one(R + (size_t)j * E + e);
         }
         zpart[jg * 64 + e] = acc;
     }
