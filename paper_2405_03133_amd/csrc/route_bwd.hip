@@ -116,14 +116,14 @@ __global__ __launch_bounds__(kDxThreads) void route_bwd_dx_kernel(const T *__res
             float dh[VEC];
 #pragma unroll
             for (int i = 0; i < VEC; ++i) dh[i] = dot_row(R + (size_t)(c + i) * E, dz, E) * invT;
-            for (int t = t0; t < t1; ++t) {
-                T *p = Xs + (size_t)t * d + c;
+            auto update = [&](uint4 q) {
                 if constexpr (sizeof(T) == 4) {
-                    float4 v = *reinterpret_cast<float4 *>(p);
-                    v.x += dh[0]; v.y += dh[1]; v.z += dh[2]; v.w += dh[3];
-                    *reinterpret_cast<float4 *>(p) = v;
+                    q.x = __float_as_uint(__uint_as_float(q.x) + dh[0]);
+                    q.y = __float_as_uint(__uint_as_float(q.y) + dh[1]);
+                    q.z = __float_as_uint(__uint_as_float(q.z) + dh[2]);
+                    q.w = __float_as_uint(__uint_as_float(q.w) + dh[3]);
+                    return q;
                 } else {
-                    uint4 q = *reinterpret_cast<uint4 *>(p);
                     uint32_t r[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
@@ -131,8 +131,20 @@ __global__ __launch_bounds__(kDxThreads) void route_bwd_dx_kernel(const T *__res
                         const float hi = __uint_as_float(r[i] & 0xffff0000u) + dh[2 * i + 1];
                         r[i] = (uint32_t)f32_to_bf16_rne(lo) | ((uint32_t)f32_to_bf16_rne(hi) << 16);
                     }
-                    *reinterpret_cast<uint4 *>(p) = make_uint4(r[0], r[1], r[2], r[3]);
+                    return make_uint4(r[0], r[1], r[2], r[3]);
                 }
+            };
+            int t = t0;
+            for (; t + 4 <= t1; t += 4) {  // four rows in flight
+                uint4 q[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) q[u] = *reinterpret_cast<const uint4 *>(Xs + (size_t)(t + u) * d + c);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) *reinterpret_cast<uint4 *>(Xs + (size_t)(t + u) * d + c) = update(q[u]);
+            }
+            for (; t < t1; ++t) {
+                T *p = Xs + (size_t)t * d + c;
+                *reinterpret_cast<uint4 *>(p) = update(*reinterpret_cast<const uint4 *>(p));
             }
         }
     } else {
