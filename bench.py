@@ -23,17 +23,56 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 
-# HBM bytes per launch (average over the launches of a step) from the rocprofv3 --pmc runs summarised in
-# profiles/hbm_traffic_C4_fwd_bwd.txt: FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the factors that make a plain
-# 1 GiB device copy read 1 GiB and write 1 GiB.  Only valid for the default launch configuration (G/U and
-# merged parameters saved, default slab budget).
-TRAFFIC_BYTES = {
-    ("C4", "merge"): 2.215e9,
-    ("C4", "scatter_dots"): 2.967e9,
-    ("C4", "gemm_gate_up"): 3.477e9,
-    ("C4", "gemm_dX"): 3.393e9,
-    ("C4", "gemm_dW_gate_up"): 3.498e9,   # two launches
+# Kernel class (as the library's event timing names it) -> pattern of the kernel names that class
+# launches, as they appear in the rocprofv3 summaries under profiles/.
+CLASS_KERNELS = {
+    "merge": r"merge_kernel",
+    "scatter_dots": r"scatter_kernel",
+    "gemm_gate_up": r"gemm2_kernel<2, 1, false, true",
+    "gemm_down": r"gemm2_kernel<1, 1, false, true",
+    "gemm_dA": r"gemm2_kernel<1, 1, false, false",
+    "gemm_dX": r"gemm2_kernel<1, 2, false, false",
+    "gemm_dW_gate_up": r"gemm2_kernel<1, 1, true, true",
+    "gemm_dW_down": r"gemm2_kernel<1, 1, true, true",
+    "swiglu_fwd": r"swiglu_fwd_kernel",
+    "swiglu_bwd": r"swiglu_bwd_kernel",
+    "route": r"route_kernel",
 }
+
+
+def measured_traffic(config, merged_save, kernel_class):
+    """HBM bytes per launch of a kernel class, read from the committed rocprofv3 --pmc summary of
+    this launch configuration (FETCH_SIZE and WRITE_SIZE scaled by what a plain device copy of
+    known size reads on the same counters; the file states the factors).  None when there is no
+    summary for the configuration or the class."""
+    import re
+    name = f"hbm_traffic_{config}_fwd_bwd{'_merged_save' if merged_save else ''}.txt"
+    path = os.path.join(ROOT, "profiles", name)
+    pat = CLASS_KERNELS.get(kernel_class)
+    if pat is None or not os.path.exists(path):
+        return None
+    with open(path) as fh:
+        for line in fh:
+            # table rows: kernel name, launches, read MiB, write MiB, total GB
+            m = re.match(r"^(lory::\S.*?)\s+(\d+)\s+([\d.]+)\s+([\d.]+)\s+([\d.]+)\s*$", line)
+            if m and re.search(pat, m.group(1)):
+                return float(m.group(5)) * 1e9
+    return None
+
+
+def algorithmic_bytes_per_step(cfg, kernel_class, merge_passes, grad_bytes):
+    """HBM bytes per step that the METHOD needs for a stage, whatever the kernels do: the merge
+    streams the expert stack once per pass (merged parameters are transient); scatter + router-weight
+    inner products stream the stack once and write every expert gradient once (per-segment weight
+    gradients are transient).  None for classes that are bound by the matrix cores."""
+    stack = 3.0 * cfg.E * cfg.d * cfg.d_ff
+    if kernel_class == "merge":
+        return merge_passes * stack * 2.0
+    if kernel_class == "scatter_dots":
+        return stack * (2.0 + grad_bytes)
+    if kernel_class == "route":
+        return cfg.tokens * cfg.d * 2.0 + cfg.d * cfg.E * 2.0 + cfg.S * cfg.E * 4.0
+    return None
 
 
 def parse_args():
@@ -45,8 +84,11 @@ def parse_args():
     ap.add_argument("--grad-dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-save", action="store_true", help="do not save G/U in the forward (backward recomputes)")
-    ap.add_argument("--no-merged-save", action="store_true",
-                    help="do not hand the forward's merged parameters to the backward (it re-merges)")
+    ap.add_argument("--merged-save", action="store_true",
+                    help="hand the forward's merged parameters to the backward in a 3*S*d*d_ff buffer instead "
+                         "of re-merging (default: merged parameters are transient; the other mode is timed "
+                         "after the headline run and reported beside it)")
+    ap.add_argument("--single-mode", action="store_true", help="do not time the other merged-parameter mode")
     ap.add_argument("--slab-mb", type=int, default=0)
     ap.add_argument("--verbose", action="store_true")
     ap.add_argument("--fwd-only", action="store_true",
@@ -84,8 +126,10 @@ def cpu_baseline(cfg, verbose=False):
     if verbose:
         print(f"[cpu] oracle {sample.tokens} tokens in {dt:.2f} s", file=sys.stderr)
     return {"value": sample.tokens / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": f"{n_seg} segments of T={cfg.T} tokens at the full d={cfg.d}, d_ff={cfg.d_ff}, E={cfg.E} "
-                      f"(route+fwd+bwd+route_bwd, fp64, {dt:.1f} s)"}
+            "sample": f"{n_seg} of the workload's {cfg.S} segments (T={cfg.T} tokens each, one sequence) at the full "
+                      f"d={cfg.d}, d_ff={cfg.d_ff}, E={cfg.E}: route+fwd+bwd+route_bwd in fp64 took {dt:.1f} s; "
+                      f"value = the sample's tokens/s, i.e. the whole workload's rate extrapolated from the "
+                      f"sample (every segment costs the same)"}
 
 
 def bench_infer(args):
@@ -196,7 +240,6 @@ def main():
     if not args.no_save and not args.fwd_only:
         G = torch.empty((cfg.tokens, cfg.d_ff), dtype=dt, device=dev)
         U = torch.empty_like(G)
-    Wbar = None if (args.no_merged_save or args.fwd_only) else lb.alloc_merged_save(shape)
     dX = torch.empty_like(X)
     dWg = torch.empty(Wg.shape, dtype=gdt, device=dev)
     dWu = torch.empty(Wu.shape, dtype=gdt, device=dev)
@@ -205,14 +248,17 @@ def main():
     hbar = torch.empty((cfg.S, cfg.d), dtype=torch.float32, device=dev)
     dR = torch.empty((cfg.d, cfg.E), dtype=torch.float32, device=dev)
 
-    def step():
-        lb.lory_route(X, R, cfg.T, w=w, hbar=hbar, d_ff=cfg.d_ff)
-        lb.lory_merged_ffn_fwd(X, w, Wg, Wu, Wd, cfg.T, Y=Y, G_save=G, U_save=U, workspace=ws_f, Wbar_save=Wbar)
-        if args.fwd_only:
-            return
-        lb.lory_merged_ffn_bwd(X, w, Wg, Wu, Wd, dY, cfg.T, G_save=G, U_save=U, dX=dX, dWg=dWg, dWu=dWu,
-                               dWd=dWd, dw=dw, grad_dtype=gdt, workspace=ws_b, Wbar_save=Wbar)
-        lb.lory_route_bwd(R, w, hbar, dw, dX, cfg.T, dR=dR, d_ff=cfg.d_ff)
+    def make_step(Wbar):
+        def step():
+            lb.lory_route(X, R, cfg.T, w=w, hbar=hbar, d_ff=cfg.d_ff)
+            lb.lory_merged_ffn_fwd(X, w, Wg, Wu, Wd, cfg.T, Y=Y, G_save=G, U_save=U, workspace=ws_f,
+                                   Wbar_save=Wbar)
+            if args.fwd_only:
+                return
+            lb.lory_merged_ffn_bwd(X, w, Wg, Wu, Wd, dY, cfg.T, G_save=G, U_save=U, dX=dX, dWg=dWg, dWu=dWu,
+                                   dWd=dWd, dw=dw, grad_dtype=gdt, workspace=ws_b, Wbar_save=Wbar)
+            lb.lory_route_bwd(R, w, hbar, dw, dX, cfg.T, dR=dR, d_ff=cfg.d_ff)
+        return step
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -222,25 +268,32 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # The step is a fixed sequence of about twenty launches on one stream; it can be captured once
-    # into a HIP graph and replayed (the library neither allocates nor synchronises, and records no
-    # memset nodes).
-    run = step
-    if args.graph:
-        step()                      # first call sets the kernels' LDS attributes (not capturable work)
+    def time_steps(step):
+        # The step is a fixed sequence of about twenty launches on one stream; it can be captured
+        # once into a HIP graph and replayed (the library neither allocates nor synchronises, and
+        # records no memset nodes).
+        run = step
+        if args.graph:
+            step()                  # first call sets the kernels' LDS attributes (not capturable work)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            run = graph.replay
+        for _ in range(args.warmup):
+            run()
         torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        run = graph.replay
-    for _ in range(args.warmup):
-        run()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    # Headline mode: merged parameters are transient (the backward re-merges) unless --merged-save.
+    merged_save = bool(args.merged_save) and not args.fwd_only
+    Wbar = lb.alloc_merged_save(shape) if merged_save else None
+    step = make_step(Wbar)
+    elapsed = time_steps(step)
     ms_per_step = 1e3 * elapsed / args.steps
     tokens_per_s = cfg.tokens * args.steps / elapsed
 
@@ -252,6 +305,16 @@ def main():
     stats = lb.lory_profile_read()
     lb.lory_profile_enable(False)
 
+    # The other merged-parameter mode of the same workload, timed the same way after the headline run.
+    other_mode_ms = None
+    if not args.fwd_only and not args.single_mode:
+        Wbar_other = None if merged_save else lb.alloc_merged_save(shape)
+        if merged_save or Wbar_other is not None:
+            other_mode_ms = 1e3 * time_steps(make_step(Wbar_other)) / args.steps
+        del Wbar_other
+
+    merge_passes = 1 if args.fwd_only else (3 if merged_save else 4)   # merge, [re-merge], scatter, inner products
+    grad_bytes = 4.0 if gdt == torch.float32 else 2.0
     kernels = {}
     for s in stats:
         n = max(s["launches"], 1)
@@ -260,24 +323,33 @@ def main():
             "ms_per_step": s["ms"] / args.steps,
             "avg_us": 1e3 * s["ms"] / n,
             "tflops": (s["flops"] / (s["ms"] * 1e-3) / 1e12) if s["ms"] > 0 else 0.0,
-            "gbs": (s["bytes"] / (s["ms"] * 1e-3) / 1e9) if s["ms"] > 0 else 0.0,
+            "design_gbs": (s["bytes"] / (s["ms"] * 1e-3) / 1e9) if s["ms"] > 0 else 0.0,
             "flops_per_launch": s["flops"] / n,
-            "bytes_per_launch": s["bytes"] / n,
+            "design_bytes_per_launch": s["bytes"] / n,
         }
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"]) if kernels else None
     roofline = None
     if dominant:
         kd = kernels[dominant]
-        if dominant.startswith("gemm"):
+        launches = max(kd["launches_per_step"], 1e-9)
+        # merge launches of the forward and of the backward re-merge are one class: passes that stream the stack
+        algo = algorithmic_bytes_per_step(cfg, dominant, 1 if (args.fwd_only or merged_save) else 2, grad_bytes)
+        if algo is None:
             roofline = {"kernel": dominant, "bound": "mfma", "achieved": kd["tflops"], "peak": PEAK_BF16_TFLOPS,
                         "unit": "TFLOP/s", "frac": kd["tflops"] / PEAK_BF16_TFLOPS}
         else:
-            roofline = {"kernel": dominant, "bound": "hbm", "achieved": kd["gbs"], "peak": PEAK_HBM_GBS,
-                        "unit": "GB/s", "frac": kd["gbs"] / PEAK_HBM_GBS}
+            per_launch = algo / launches
+            gbs = per_launch / (kd["avg_us"] * 1e-6) / 1e9
+            roofline = {"kernel": dominant, "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS,
+                        "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                        "algorithmic_bytes_per_launch": per_launch,
+                        "design_bytes_per_launch": kd["design_bytes_per_launch"],
+                        "design_gbs": kd["design_gbs"]}
         roofline["avg_launch_us"] = kd["avg_us"]
-        default_launch = not (args.no_save or args.no_merged_save or args.slab_mb or args.grad_dtype != "bf16"
-                              or args.fwd_only)
-        roofline["traffic"] = TRAFFIC_BYTES.get((args.config, dominant)) if default_launch else None
+        default_launch = not (args.no_save or args.slab_mb or args.grad_dtype != "bf16" or args.fwd_only)
+        roofline["traffic"] = measured_traffic(args.config, merged_save, dominant) if default_launch else None
+        if roofline["traffic"] and algo is not None:
+            roofline["traffic_over_algorithmic"] = roofline["traffic"] / (algo / launches)
 
     # The paper's utilisation analysis (appendix on expert utilisation) calls an expert activated for
     # an input when its routing weight exceeds 2/E; logged for the synthetic router, whose N(0, 0.02)
@@ -286,7 +358,7 @@ def main():
                "mean_max_w": float(w.max(dim=1).values.mean().item())}
     with_bwd = not args.fwd_only
     gemm_tflops = cfg.gemm_flops(with_bwd) / (ms_per_step * 1e-3) / 1e12
-    all_tflops = (cfg.gemm_flops(with_bwd) + cfg.merge_flops(4 if with_bwd else 1)) / (ms_per_step * 1e-3) / 1e12
+    all_tflops = (cfg.gemm_flops(with_bwd) + cfg.merge_flops(merge_passes)) / (ms_per_step * 1e-3) / 1e12
     out = {
         "metric": "merged-MoE-FFN tokens/sec/GPU (fwd+bwd) + % bf16 MFMA peak",
         "value": tokens_per_s,
@@ -302,7 +374,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} L={cfg.L} T={cfg.T} d={cfg.d} d_ff={cfg.d_ff} E={cfg.E} "
                                f"{cfg.dtype} {'route+fwd' if args.fwd_only else 'route+fwd+bwd+route_bwd'}, grad_dtype={args.grad_dtype}, "
-                               f"save_GU={not args.no_save}, save_merged={Wbar is not None}, "
+                               f"save_GU={not args.no_save}, save_merged={merged_save}, "
                                f"hip_graph={args.graph}",
                    "tokens": cfg.tokens, "segments": cfg.S},
         "gemm_tflops": gemm_tflops,
@@ -312,6 +384,8 @@ def main():
         "routing": routing,
         "kernels": kernels,
     }
+    if other_mode_ms is not None:
+        out["ms_per_step_merged_save" if not merged_save else "ms_per_step_no_merged_save"] = other_mode_ms
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, args.verbose)
     else:
@@ -319,7 +393,8 @@ def main():
     if args.verbose:
         for k, v in kernels.items():
             print(f"[kernel] {k:18s} {v['launches_per_step']:6.1f} launches/step {v['ms_per_step']:8.3f} ms/step "
-                  f"avg {v['avg_us']:8.1f} us  {v['tflops']:8.1f} TFLOP/s {v['gbs']:8.0f} GB/s", file=sys.stderr)
+                  f"avg {v['avg_us']:8.1f} us  {v['tflops']:8.1f} TFLOP/s {v['design_gbs']:8.0f} GB/s (design bytes)",
+                  file=sys.stderr)
         print(f"[bench] {ms_per_step:.3f} ms/step, {tokens_per_s / 1e6:.3f} Mtok/s, GEMM {gemm_tflops:.0f} TFLOP/s",
               file=sys.stderr)
     print(json.dumps(out))

@@ -24,6 +24,12 @@
  *     and the saved activations: LORY_F32 (fp32 arithmetic throughout) or
  *     LORY_BF16 (bf16 operands, fp32 accumulation on the matrix cores).
  *     Routing weights w / dw and hbar are always fp32.
+ *   - Host-side state (the slab budget, the optional event timing, one-time
+ *     kernel attribute set-up) is process-global and unsynchronised: calls
+ *     into the library from several host threads must be serialised by the
+ *     caller.  Workspace sizes depend on the slab budget in force when
+ *     lory_workspace_bytes is called; keep it unchanged until the call that
+ *     uses the workspace has returned.
  *   - Shape rules: every dimension > 0, L % T == 0 (the paper's listing uses
  *     N = L // T with a reshape, so a ragged tail has no defined meaning),
  *     E <= 64.  LORY_BF16 additionally needs d % 64 == 0, d_ff % 64 == 0 and
@@ -87,7 +93,9 @@ int lory_set_slab_budget(size_t bytes);
  * lory_profile_read waits for the recorded events, sums them per class into
  * out[0..*n_out) (at most max_out entries; classes without launches are
  * skipped) and clears the records.  Host-side state is process-global and not
- * thread-safe; event objects are created on demand and reused.
+ * thread-safe.  The event objects (4096, i.e. 2048 timed launches between two
+ * reads; further launches go untimed) are created by lory_profile_enable(1),
+ * never inside a launch, and reused.
  */
 typedef struct {
     char name[32];   /* kernel class, e.g. "gemm_gate_up", "merge", "scatter_dots" */
@@ -210,8 +218,12 @@ int lory_dense_ffn_fwd(const lory_shape *shape, const void *X, const void *Wbar,
  *      merged parameters of all segments, laid out [Wg_bar | Wu_bar | Wd_bar],
  *      each [S, rows, cols] like one expert matrix (LORY_ERR_SHAPE if the
  *      shape does not support it).
- * Without Wbar_save the merged parameters are never materialised as a whole:
- * they pass through a bounded slab inside the workspace.
+ * Without Wbar_save the merged parameters are transient: they are produced
+ * block by block into a slab inside the workspace and consumed from there by
+ * the projections.  The slab is bounded by lory_set_slab_budget; with the
+ * default budget of 6 GiB and a shape whose S * d * d_ff * 2 * 2 bytes fit, one
+ * block is a whole matrix for all S segments (gate and up together at the
+ * headline shape: 2.95 GB resident while the projections run).
  */
 int lory_merged_ffn_fwd(const lory_shape *shape, const void *X, const float *w,
                         const void *Wg, const void *Wu, const void *Wd,
@@ -234,9 +246,13 @@ int lory_merged_ffn_fwd(const lory_shape *shape, const void *X, const float *w,
  *      LORY_BF16); dw [S, E] fp32 for all segments including the first.
  *      accumulate = 0 overwrites dWg/dWu/dWd, 1 adds to them.  dX and dw are
  *      always overwritten.
- * The per-segment weight gradients dWx_bar are never materialised as a
- * whole.  Reductions across workgroups use a fixed order: two calls on the
- * same inputs give bit-identical results.
+ * The per-segment weight gradients dWx_bar are transient: they pass, one
+ * block of d_ff columns at a time, through the slab inside the workspace
+ * (bf16; bounded by lory_set_slab_budget - with the default budget and the
+ * headline shape one block is all of d_ff, i.e. dWd_bar, dWg_bar and dWu_bar of
+ * all S segments, 4.4 GB, are resident between the weight-gradient GEMMs and
+ * the scatter).  Reductions across workgroups use a fixed order: two calls on
+ * the same inputs give bit-identical results.
  */
 int lory_merged_ffn_bwd(const lory_shape *shape, const void *X, const float *w,
                         const void *Wg, const void *Wu, const void *Wd,

@@ -21,8 +21,11 @@ hipError_t launch_gu_t(hipStream_t st, const gemm::Params &p, const EpiGU &d)
 
 hipError_t launch_gu(hipStream_t st, const gemm::Params &p, const EpiGU &e)
 {
+    // Two output modes: G and U (the activation is then a streaming pass over them), or the
+    // activation alone.  A three-plane epilogue (G, U and A at once) is not instantiated: it needs
+    // scratch memory for spilled registers and measured slower than the separate pass.
     const bool save = e.G != nullptr, act = e.Act != nullptr;
-    if (save && act) return launch_gu_t<true, true>(st, p, e);
+    if (save == act) return hipErrorInvalidValue;
     if (act) return launch_gu_t<false, true>(st, p, e);
     return launch_gu_t<true, false>(st, p, e);
 }

@@ -28,16 +28,28 @@ const char *const kNames[kNumClasses] = {"route",     "merge",     "gemm_gate_up
                                          "gemm_dA",   "swiglu_bwd", "gemm_dX",   "gemm_dW_gate_up",
                                          "gemm_dW_down", "scatter_dots", "dw_reduce", "route_bwd", "dense_skinny"};
 
+// Events are created when timing is switched on (and by lory_profile_read, which returns
+// them to the pool), never inside a launch: a launch only takes events from the pool and
+// goes untimed when the pool is empty.
+constexpr size_t kPoolEvents = 4096;   // 2048 timed launches between two reads
+
 hipEvent_t get_event()
 {
-    if (!g_pool.empty()) {
-        hipEvent_t e = g_pool.back();
-        g_pool.pop_back();
-        return e;
-    }
-    hipEvent_t e = nullptr;
-    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    if (g_pool.empty()) return nullptr;
+    hipEvent_t e = g_pool.back();
+    g_pool.pop_back();
     return e;
+}
+
+void fill_pool()
+{
+    g_pool.reserve(kPoolEvents);
+    g_records.reserve(kPoolEvents / 2);
+    while (g_pool.size() < kPoolEvents) {
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) break;
+        g_pool.push_back(e);
+    }
 }
 
 }  // namespace
@@ -51,9 +63,9 @@ Range::Range(hipStream_t st, int cls, double flops, double bytes) : st_(st), idx
     r.cls = cls;
     r.flops = flops;
     r.bytes = bytes;
+    if (g_pool.size() < 2 || g_records.size() == g_records.capacity()) return;  // untimed launch
     r.start = get_event();
     r.stop = get_event();
-    if (!r.start || !r.stop) return;
     hipEventRecord(r.start, st);
     g_records.push_back(r);
     idx_ = (int)g_records.size() - 1;
@@ -67,6 +79,7 @@ Range::~Range()
 int set_enabled(int on)
 {
     g_on = on != 0;
+    if (g_on) fill_pool();
     return LORY_OK;
 }
 

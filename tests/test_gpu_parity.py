@@ -11,17 +11,17 @@ import torch
 from oracle import lory_oracle as orc
 from paper_2405_03133_amd import binding as lb
 from paper_2405_03133_amd.inputs import CONFIGS, LoryConfig, make_inputs, make_routing_weights, round_to_bf16
+from parity_util import check, host, rel_l2
 
 pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-5, "bf16": 1e-2}
-
-
-def rel_l2(got, ref):
-    got = np.asarray(got, dtype=np.float64)
-    ref = np.asarray(ref, dtype=np.float64)
-    den = np.linalg.norm(ref)
-    return float(np.linalg.norm(got - ref) / (den if den > 0 else 1.0))
+# Router-weight gradient of the whole layer: dR = sum_s hbar_s^T dz_s, dz = e * (de - <e, de>), de = the
+# FFN's dw shifted by one segment.  It inherits the error of dw (the bar above; the centring
+# de - <e, de> is well conditioned for these inputs, ||de|| / ||de - <e, de>|| is about 1) and of the
+# fp32 softmax and segment means of the forward (1e-7 relative), hence 1e-4 instead of 1e-5 for the
+# fp32 configuration, as for lory_route_bwd on its own.
+DR_TOL = {"f32": 1e-4, "bf16": 1e-2}
 
 
 def tdtype(cfg):
@@ -30,10 +30,6 @@ def tdtype(cfg):
 
 def to_dev(a, cfg):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda().to(tdtype(cfg)).contiguous()
-
-
-def host(t):
-    return t.detach().float().cpu().numpy().astype(np.float64)
 
 
 def run_layer(cfg, t, w_override=None, save=True, grad_dtype=torch.float32, merged_save=False):
@@ -74,11 +70,9 @@ def oracle_layer(cfg, t, w_used):
 
 
 def compare(cfg, got, ref, names, tol):
-    errs = {k: rel_l2(got[k].reshape(ref[k].shape), ref[k]) for k in names}
-    print(f"[parity] {cfg.name}: " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
-    for k, v in errs.items():
-        assert np.isfinite(v) and v <= tol, (cfg.name, k, v)
-    return errs
+    """Whole-tensor rel-L2, worst-row rel-L2 and largest absolute error of every named tensor
+    (parity_util.check: the last two are what a single wrong tile or ragged last block trips)."""
+    return {k: check(f"{cfg.name} {k}", got[k], ref[k], tol) for k in names}
 
 
 ALL = ("Y", "G", "U", "dX", "dWg", "dWu", "dWd", "dw")
@@ -210,10 +204,15 @@ def test_bf16_recompute_bf16_grads_and_accumulate(default_budget):
         lb.lory_merged_ffn_bwd(X, w, Wg, Wu, Wd, dY, cfg.T, dWg=base[0], dWu=base[1], dWd=base[2],
                                accumulate=True, grad_dtype=gd)
         torch.cuda.synchronize()
-        tol = 2e-2 if gd == torch.bfloat16 else TOL["bf16"]
-        assert rel_l2(host(base[0]), ref["dWg"] + 0.5) <= tol
-        assert rel_l2(host(base[1]), ref["dWu"] - 0.25) <= tol
-        assert rel_l2(host(base[2]), ref["dWd"] + 2.0) <= tol
+        for got_sum, c, key in ((base[0], 0.5, "dWg"), (base[1], -0.25, "dWu"), (base[2], 2.0, "dWd")):
+            # the increment itself is held to the bf16 bar; a bf16 sum c + dW is stored with one more
+            # rounding, uniform within half a bf16 spacing (<= 2^-7 |c + dW|), i.e. an rms error of at
+            # most 2^-7 / sqrt(12) of the stored values, measured here against the increment
+            rms = lambda a: float(np.sqrt(np.mean(np.square(a))))
+            store = (2.0 ** -7 / np.sqrt(12.0)) * rms(ref[key] + c) / rms(ref[key]) if gd == torch.bfloat16 else 0.0
+            err = rel_l2(host(got_sum) - c, ref[key])
+            print(f"[parity] accumulate {key} {gd}: {err:.2e} (bar {TOL['bf16'] + store:.2e})", flush=True)
+            assert err <= TOL["bf16"] + store, (key, gd, err)
 
 
 def test_bf16_onehot_and_determinism(default_budget):
@@ -322,7 +321,7 @@ def test_whole_layer_gradient_fp32():
     ref = orc.layer_bwd(t["X"], t["R"], t["Wg"], t["Wu"], t["Wd"], t["dY"], cfg.T)
     got = {"dX": host(dX), "dR": host(dR), "dWg": host(dWg), "dWu": host(dWu), "dWd": host(dWd)}
     compare(cfg, got, ref, ("dX", "dWg", "dWu", "dWd"), 2e-5)
-    compare(cfg, got, ref, ("dR",), 1e-3)   # dR inherits the fp32 rounding of dw through a cancelling sum
+    compare(cfg, got, ref, ("dR",), DR_TOL["f32"])
     assert np.linalg.norm(ref["dR"]) > 0
 
 
@@ -485,8 +484,7 @@ def test_autograd_wrapper_matches_oracle_layer_gradient(cfg):
            "dWu": host(leaves["Wu"].grad), "dWd": host(leaves["Wd"].grad), "dR": host(leaves["R"].grad)}
     ref = dict(ref, Y=ref_y)
     compare(cfg, got, ref, ("Y", "dX", "dWg", "dWu", "dWd"), tol)
-    # dR inherits the rounding of dw through a cancelling sum (and bf16 storage of the gradient)
-    compare(cfg, got, ref, ("dR",), 1e-3 if cfg.dtype == "f32" else 3e-2)
+    compare(cfg, got, ref, ("dR",), DR_TOL[cfg.dtype])
 
 
 @pytest.mark.parametrize("L,lens", [(96, [96, 1, 37, 64]), (512, [512, 1, 300, 257])], ids=["short", "long"])
