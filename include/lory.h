@@ -207,6 +207,27 @@ int lory_dense_ffn_fwd(const lory_shape *shape, const void *X, const void *Wbar,
                        void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * lory_dense_ffn_fwd for callers that cannot allocate device memory or carry
+ * a workspace: code under HIP graph capture, tight serving loops (one decode
+ * step per call), harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical results; what lory_dense_ffn_fwd keeps in the
+ * caller's workspace (partial sums of the K splits, or the activation block of
+ * the matrix-core path) lives in a 16 MiB array in device memory that the
+ * library itself holds (one copy per GPU, for the life of the process).
+ * Returns LORY_ERR_WORKSPACE, before any launch, when
+ * lory_workspace_bytes(shape, LORY_PASS_DENSE) exceeds 16 MiB (16777216 bytes):
+ * at d = 2048, d_ff = 5632 a decode step of one token per sequence needs about
+ * 6 MiB and two tokens per sequence about 12 MiB, whatever the batch (the K
+ * split shrinks as the batch grows); larger calls take lory_dense_ffn_fwd.
+ * The call allocates nothing and clears nothing (the kernels write every
+ * value of the array before they read it).  All calls on one GPU share that
+ * GPU's array: calls that overlap on one GPU (different streams, or different
+ * host threads) race; calls on one stream do not.
+ */
+int lory_dense_ffn_fwd_static(const lory_shape *shape, const void *X, const void *Wbar, void *Y,
+                              void *stream);
+
+/*
  * Merged FFN forward (Eq. 1 / Eq. 2 with SwiGLU experts):
  *   for every segment s (S = B*N of them, T tokens each):
  *     Wg_bar = sum_e w[s,e] Wg[e],  Wu_bar, Wd_bar likewise

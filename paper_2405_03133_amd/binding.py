@@ -27,7 +27,7 @@ LORY_PASS_FWD, LORY_PASS_BWD, LORY_PASS_DENSE = 0, 1, 2
 EXPORTS = ("lory_status_string", "lory_version", "lory_set_slab_budget", "lory_profile_enable",
            "lory_profile_read", "lory_merged_save_bytes", "lory_workspace_bytes", "lory_route",
            "lory_route_bwd", "lory_merged_ffn_fwd", "lory_merged_ffn_bwd", "lory_prompt_merge",
-           "lory_dense_ffn_fwd")
+           "lory_dense_ffn_fwd", "lory_dense_ffn_fwd_static")
 
 
 class LoryShape(ctypes.Structure):
@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
         L.lory_prompt_merge.restype = ci
         L.lory_dense_ffn_fwd.argtypes = [sp, vp, vp, vp, vp, sz, vp]
         L.lory_dense_ffn_fwd.restype = ci
+        L.lory_dense_ffn_fwd_static.argtypes = [sp, vp, vp, vp, vp]
+        L.lory_dense_ffn_fwd_static.restype = ci
         L.lory_merged_save_bytes.argtypes = [sp, ctypes.POINTER(sz)]
         L.lory_merged_save_bytes.restype = ci
         L.lory_merged_ffn_fwd.argtypes = [sp] + [vp] * 10 + [sz, vp]
@@ -257,6 +259,17 @@ def lory_dense_ffn_fwd(X: torch.Tensor, Wbar: torch.Tensor, d_ff: int, Y: Option
         workspace = alloc_workspace(shape, LORY_PASS_DENSE, X.device)
     _check(lib().lory_dense_ffn_fwd(ctypes.byref(shape), _ptr(X), _ptr(Wbar), _ptr(Y), _ptr(workspace),
                                     workspace.numel(), _stream()), "lory_dense_ffn_fwd")
+    return Y
+
+
+def lory_dense_ffn_fwd_static(X: torch.Tensor, Wbar: torch.Tensor, d_ff: int, Y: torch.Tensor) -> torch.Tensor:
+    """lory_dense_ffn_fwd without a workspace argument (library-held scratch); Y is the caller's."""
+    B, L, d = X.shape
+    if Wbar.dtype != X.dtype or Wbar.numel() != 3 * B * d * d_ff:
+        raise ValueError("Wbar must hold 3*B*d*d_ff elements of X's dtype")
+    shape = make_shape(B, L, L, d, d_ff, 1, X.dtype)
+    _check(lib().lory_dense_ffn_fwd_static(ctypes.byref(shape), _ptr(X), _ptr(Wbar), _ptr(Y), _stream()),
+           "lory_dense_ffn_fwd_static")
     return Y
 
 

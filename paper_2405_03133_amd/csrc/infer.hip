@@ -237,8 +237,9 @@ SkinnyPlan skinny_plan(const Dims &m)
     p.vec2 = (m.d % Ld<T>::vec == 0) ? Ld<T>::vec : 1;
     p.ks1 = choose_ksplit(m.d, m.dff, m.B, p.vec1);
     p.ks2 = choose_ksplit(m.dff, m.d, m.B, p.vec2);
-    p.part1 = (size_t)p.ks1 * m.B * 2 * kMaxTok * m.dff;
-    p.part2 = (size_t)p.ks2 * m.B * kMaxTok * m.d;
+    const int mt = m.L < kMaxTok ? m.L : kMaxTok;   // tokens of the largest pass
+    p.part1 = (size_t)p.ks1 * m.B * 2 * mt * m.dff;
+    p.part2 = (size_t)p.ks2 * m.B * mt * m.d;
     return p;
 }
 
@@ -306,7 +307,43 @@ int skinny_ffn(const Dims &m, const T *X, const T *Wbar, T *Y, void *ws, hipStre
 
 bool gemm_path(const Dims &m) { return m.dtype == LORY_BF16 && m.L % 64 == 0; }
 
+// Scratch of lory_dense_ffn_fwd_static: the partial sums (or the activation block) that
+// lory_dense_ffn_fwd keeps in the caller's workspace, held by the library instead.  Every GPU
+// the library runs on holds its own copy of the array at its own address until the process
+// ends; in host code the array's name is only a handle for hipGetSymbolAddress, the address
+// looked up per device is what launches receive.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void *g_scratch_addr[kMaxDevices];  // device address of `scratch` per device ordinal, looked up once
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LORY_ERR_DEVICE;
+    if (!g_scratch_addr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return LORY_ERR_DEVICE;
+        g_scratch_addr[dev] = ptr;
+    }
+    *out = g_scratch_addr[dev];
+    return LORY_OK;
+}
+
 }  // namespace
+
+size_t dense_static_scratch_limit() { return kStaticScratchBytes; }
+
+int dense_ffn_fwd_static(const Dims &m, const void *X, const void *Wbar, void *Y, hipStream_t st)
+{
+    if (dense_workspace_bytes(m) > kStaticScratchBytes) return LORY_ERR_WORKSPACE;
+    void *ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != LORY_OK) return rc;
+    // Every value the kernels read from the scratch is written earlier in the same call, so
+    // nothing has to be cleared between calls.
+    return dense_ffn_fwd(m, X, Wbar, Y, ws, st);
+}
 
 size_t dense_workspace_bytes(const Dims &m)
 {

@@ -175,6 +175,18 @@ int lory_dense_ffn_fwd(const lory_shape *shape, const void *X, const void *Wbar,
     return lory::dense_ffn_fwd(m, X, Wbar, Y, workspace, (hipStream_t)stream);
 }
 
+int lory_dense_ffn_fwd_static(const lory_shape *shape, const void *X, const void *Wbar, void *Y, void *stream)
+{
+    const int rc = check_shape_infer(shape);
+    if (rc != LORY_OK) return rc;
+    if (!X || !Wbar || !Y) return LORY_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Wbar) || !aligned16(Y)) return LORY_ERR_ALIGN;
+    const Dims m = lory::make_dims(*shape);
+    if (lory::align_up(lory::dense_workspace_bytes(m), 256) > lory::dense_static_scratch_limit())
+        return LORY_ERR_WORKSPACE;
+    return lory::dense_ffn_fwd_static(m, X, Wbar, Y, (hipStream_t)stream);
+}
+
 int lory_merged_ffn_fwd(const lory_shape *shape, const void *X, const float *w, const void *Wg,
                         const void *Wu, const void *Wd, void *Y, void *G_save, void *U_save,
                         void *Wbar_save, void *workspace, size_t workspace_bytes, void *stream)

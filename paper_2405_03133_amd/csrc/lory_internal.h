@@ -87,6 +87,8 @@ int f32_merge_all(const Dims &m, const float *w, const float *Wg, const float *W
 // ---- inference with prompt-only routing (infer.hip)
 size_t dense_workspace_bytes(const Dims &m);
 int dense_ffn_fwd(const Dims &m, const void *X, const void *Wbar, void *Y, void *ws, hipStream_t st);
+size_t dense_static_scratch_limit();
+int dense_ffn_fwd_static(const Dims &m, const void *X, const void *Wbar, void *Y, hipStream_t st);
 
 // ---- bf16 path (ffn_bf16.hip)
 int bf16_merge_all(const Dims &m, const float *w, const void *Wg, const void *Wu, const void *Wd,
