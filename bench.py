@@ -90,6 +90,9 @@ def parse_args():
                          "after the headline run and reported beside it)")
     ap.add_argument("--single-mode", action="store_true", help="do not time the other merged-parameter mode")
     ap.add_argument("--slab-mb", type=int, default=0)
+    ap.add_argument("--fused", type=int, default=-1, choices=[-1, 0, 1],
+                    help="lory_set_fused_merge: 0 slab pipeline only (the library's default), 1 merge inside the "
+                         "GEMM wherever the shape fits; -1 leaves the default")
     ap.add_argument("--verbose", action="store_true")
     ap.add_argument("--fwd-only", action="store_true",
                     help="time lory_route + lory_merged_ffn_fwd only (the forward configurations of the sweep)")
@@ -215,6 +218,8 @@ def main():
     dev = torch.device("cuda:0")
     if args.slab_mb:
         lb.lory_set_slab_budget(args.slab_mb << 20)
+    if args.fused >= 0:
+        lb.lory_set_fused_merge(args.fused)
     dt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     gdt = torch.float32 if (args.grad_dtype == "f32" or cfg.dtype == "f32") else torch.bfloat16
 
@@ -346,7 +351,8 @@ def main():
                         "design_bytes_per_launch": kd["design_bytes_per_launch"],
                         "design_gbs": kd["design_gbs"]}
         roofline["avg_launch_us"] = kd["avg_us"]
-        default_launch = not (args.no_save or args.slab_mb or args.grad_dtype != "bf16" or args.fwd_only)
+        default_launch = not (args.no_save or args.slab_mb or args.grad_dtype != "bf16" or args.fwd_only
+                              or args.fused >= 0)
         roofline["traffic"] = measured_traffic(args.config, merged_save, dominant) if default_launch else None
         if roofline["traffic"] and algo is not None:
             roofline["traffic_over_algorithmic"] = roofline["traffic"] / (algo / launches)
@@ -375,7 +381,7 @@ def main():
         "config": {"workload": f"{cfg.name}: B={cfg.B} L={cfg.L} T={cfg.T} d={cfg.d} d_ff={cfg.d_ff} E={cfg.E} "
                                f"{cfg.dtype} {'route+fwd' if args.fwd_only else 'route+fwd+bwd+route_bwd'}, grad_dtype={args.grad_dtype}, "
                                f"save_GU={not args.no_save}, save_merged={merged_save}, "
-                               f"hip_graph={args.graph}",
+                               f"hip_graph={args.graph}, fused_merge={'default' if args.fused < 0 else args.fused}",
                    "tokens": cfg.tokens, "segments": cfg.S},
         "gemm_tflops": gemm_tflops,
         "pct_bf16_mfma_peak_gemm_only": 100.0 * gemm_tflops / PEAK_BF16_TFLOPS,

@@ -85,6 +85,21 @@ const char *lory_version(void);
 int lory_set_slab_budget(size_t bytes);
 
 /*
+ * Tuning knob (process-global, host-only): run the token contractions of
+ * LORY_BF16 shapes with the merge INSIDE the GEMM (Eq. 2's theta_bar formed
+ * tile by tile on chip and consumed there: no merged parameter reaches HBM, in
+ * the forward or in the backward's re-merge) instead of the slab pipeline.
+ *   0  never (default: the slab pipeline measured faster at every benchmark
+ *      shape; the fused kernel is bound by the L2 -> CU path)
+ *   1  wherever the shape fits the kernel: T in {64, 128, 256}, E <= 32,
+ *      B*L a multiple of 1024 (512 for T <= 128), no Wbar_save given
+ * The LORY_FUSED environment variable sets the initial value.  Changes what
+ * lory_workspace_bytes reports (forward pass), so set it before sizing a
+ * workspace.  Returns LORY_ERR_SHAPE for other values.
+ */
+int lory_set_fused_merge(int mode);
+
+/*
  * Optional timing of the hot path's kernels, by class, with HIP events on the
  * caller's stream (the measurement model is the paper's Appendix B: GEMM work
  * 6*tokens*d*d_ff per pass direction, merge-class work 6*E*d*d_ff per segment

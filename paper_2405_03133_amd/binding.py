@@ -24,7 +24,7 @@ LORY_ERR_NULL, LORY_ERR_SHAPE, LORY_ERR_DTYPE, LORY_ERR_ALIGN, LORY_ERR_WORKSPAC
 LORY_F32, LORY_BF16 = 0, 1
 LORY_PASS_FWD, LORY_PASS_BWD, LORY_PASS_DENSE = 0, 1, 2
 
-EXPORTS = ("lory_status_string", "lory_version", "lory_set_slab_budget", "lory_profile_enable",
+EXPORTS = ("lory_status_string", "lory_version", "lory_set_slab_budget", "lory_set_fused_merge", "lory_profile_enable",
            "lory_profile_read", "lory_merged_save_bytes", "lory_workspace_bytes", "lory_route",
            "lory_route_bwd", "lory_merged_ffn_fwd", "lory_merged_ffn_bwd", "lory_prompt_merge",
            "lory_dense_ffn_fwd", "lory_dense_ffn_fwd_static")
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.lory_version.restype = ctypes.c_char_p
         L.lory_set_slab_budget.argtypes = [sz]
         L.lory_set_slab_budget.restype = ci
+        L.lory_set_fused_merge.argtypes = [ci]
+        L.lory_set_fused_merge.restype = ci
         L.lory_profile_enable.argtypes = [ci]
         L.lory_profile_enable.restype = ci
         L.lory_profile_read.argtypes = [ctypes.POINTER(LoryKernelStat), ci, ctypes.POINTER(ci)]
@@ -133,6 +135,11 @@ def _check(status: int, where: str) -> None:
 
 def lory_set_slab_budget(nbytes: int) -> None:
     _check(lib().lory_set_slab_budget(int(nbytes)), "lory_set_slab_budget")
+
+
+def lory_set_fused_merge(mode: int) -> None:
+    """0 = slab pipeline only (default), 1 = merge inside the GEMM wherever the shape fits the kernel."""
+    _check(lib().lory_set_fused_merge(int(mode)), "lory_set_fused_merge")
 
 
 def lory_profile_enable(on: bool) -> None:

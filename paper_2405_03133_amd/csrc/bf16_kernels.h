@@ -5,6 +5,7 @@
 #include "gemm_bf16.h"
 #include "gemm2_bf16.h"
 #include "merge_scatter_bf16.h"
+#include "fused_bf16.h"
 
 namespace lory {
 namespace k {
@@ -113,6 +114,10 @@ hipError_t launch_dw_reduce(hipStream_t st, const float *partials, int slots, in
                             float *dw, int S, int E);
 int scatter_grid();                       // workgroups the scatter kernel is launched with
 void scatter_partial_dims(int S, int E, int *rows, int *cols);
+
+// merge inside the GEMM (fused_bf16.h): C = sum over nsrc sources of A_q * Wbar_q(segment of the row)
+bool fused_fits(const fmg::Params &p);
+hipError_t launch_fused(hipStream_t st, const fmg::Params &p, int nsrc, bool w_nc);
 
 hipError_t launch_gu(hipStream_t st, const gemm::Params &p, const EpiGU &e);     // X * [Wg_bar | Wu_bar]
 hipError_t launch_down(hipStream_t st, const gemm::Params &p, const EpiStore &e);  // A * Wd_bar

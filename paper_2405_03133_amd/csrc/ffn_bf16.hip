@@ -47,6 +47,57 @@ size_t slab_budget_bytes()
     return g_slab_budget;
 }
 
+// Whether the token contractions take the merge-inside-the-GEMM kernels (fused_bf16.h) instead of
+// the slab pipeline, for shapes that fit them.  Off by default: at every benchmark shape measured
+// so far the slab pipeline is faster (the fused kernel is bound by the L2 -> CU path).
+int g_fused_mode = -1;  // -1 = not initialised yet
+
+int fused_mode()
+{
+    if (g_fused_mode < 0) {
+        int mode = 0;
+        if (const char *env = getenv("LORY_FUSED")) {
+            const long v = atol(env);
+            if (v == 0 || v == 1) mode = (int)v;
+        }
+        g_fused_mode = mode;
+    }
+    return g_fused_mode;
+}
+
+fmg::Params fused_params(const Dims &m, const bf *A0, const bf *A1, int lda, const bf *W0, const bf *W1, int ldw,
+                         const float *w, int N, int K, bf *C, int ldc)
+{
+    fmg::Params p = {};
+    p.A[0] = A0; p.A[1] = A1; p.lda[0] = p.lda[1] = lda;
+    p.W[0] = W0; p.W[1] = W1;
+    p.expert_stride = m.D; p.ldw = ldw;
+    p.w = w; p.E = m.E; p.T = m.T; p.tokens = (int)m.tokens;
+    p.N = N; p.K = K; p.C = C; p.ldc = ldc;
+    return p;
+}
+
+bool use_fused(const Dims &m)
+{
+    const int mode = fused_mode();
+    if (mode == 0 || m.tokens > 0x7fffffffL) return false;
+    // every contraction of the layer has N and K in {d, d_ff}
+    const fmg::Params a = fused_params(m, nullptr, nullptr, m.d, nullptr, nullptr, m.dff, nullptr, m.dff, m.d,
+                                       nullptr, m.dff);
+    const fmg::Params b = fused_params(m, nullptr, nullptr, m.dff, nullptr, nullptr, m.d, nullptr, m.d, m.dff,
+                                       nullptr, m.d);
+    return k::fused_fits(a) && k::fused_fits(b);
+}
+
+// One fused contraction: C = sum over sources of A_q * Wbar_q(segment), merged on chip.
+hipError_t fused_gemm(hipStream_t st, const Dims &m, int cls, const fmg::Params &p, int nsrc, bool w_nc)
+{
+    const double D = (double)p.N * p.K;
+    prof::Range r(st, cls, nsrc * (2.0 * p.tokens * D + 4.0 * m.S * m.E * D),
+                  2.0 * (nsrc * ((double)m.E * D + (double)p.tokens * p.K) + (double)p.tokens * p.N));
+    return k::launch_fused(st, p, nsrc, w_nc);
+}
+
 // Largest multiple of `gran` that is <= limit and <= full, at least gran.
 int block_width(size_t budget, size_t bytes_per_unit, int full, int gran)
 {
@@ -165,6 +216,13 @@ hipError_t gate_up_block(hipStream_t st, const Dims &m, int S, const bf *X, cons
 
 }  // namespace
 
+int set_fused_mode(int mode)
+{
+    if (mode != 0 && mode != 1) return LORY_ERR_SHAPE;
+    g_fused_mode = mode;
+    return LORY_OK;
+}
+
 int set_slab_budget(size_t bytes)
 {
     if (bytes < ((size_t)64 << 10)) return LORY_ERR_SHAPE;
@@ -182,7 +240,11 @@ size_t bf16_merged_save_bytes(const Dims &m)
 size_t bf16_workspace_bytes(const Dims &m, int pass)
 {
     const Plan p = make_plan(m);
-    if (pass == LORY_PASS_FWD) return p.act + p.slab_fwd;
+    if (pass == LORY_PASS_FWD) {
+        // fused path: G and U of all tokens when the caller does not keep them
+        const size_t gu = use_fused(m) ? 2 * p.act : 0;
+        return p.act + (p.slab_fwd > gu ? p.slab_fwd : gu);
+    }
     // dG, dU, Act, recomputed G and U, slabs, router-weight partial sums
     return 5 * p.act + p.slab_bwd + p.partials;
 }
@@ -201,6 +263,22 @@ int bf16_ffn_fwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
     bf *Act = (bf *)ws;
     bf *slab = (bf *)((char *)ws + pl.act);
     const long TD = (long)m.T * m.d, TF = (long)m.T * m.dff;
+
+    if (!Wbar && m.S <= pl.Sc && use_fused(m)) {
+        // merged parameters never leave the chip: three fused contractions and one SwiGLU pass
+        bf *Gf = G ? G : slab, *Uf = U ? U : (bf *)((char *)slab + pl.act);
+        LORY_TRY(fused_gemm(st, m, prof::kFusedGU,
+                            fused_params(m, X, nullptr, m.d, Wg, nullptr, m.dff, w, m.dff, m.d, Gf, m.dff), 1, true));
+        LORY_TRY(fused_gemm(st, m, prof::kFusedGU,
+                            fused_params(m, X, nullptr, m.d, Wu, nullptr, m.dff, w, m.dff, m.d, Uf, m.dff), 1, true));
+        {
+            prof::Range r(st, prof::kSwigluFwd, 4.0 * m.tokens * m.dff, 2.0 * 3.0 * m.tokens * m.dff);
+            LORY_TRY(k::launch_swiglu_fwd(st, Gf, Uf, Act, m.tokens, m.dff, 0, m.dff));
+        }
+        LORY_TRY(fused_gemm(st, m, prof::kFusedDown,
+                            fused_params(m, Act, nullptr, m.dff, Wd, nullptr, m.d, w, m.d, m.dff, Y, m.d), 1, true));
+        return LORY_OK;
+    }
 
     for (int s0 = 0; s0 < m.S; s0 += pl.Sc) {
         const int S = (m.S - s0 < pl.Sc) ? (m.S - s0) : pl.Sc;
@@ -308,6 +386,9 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
     const long TD = (long)m.T * m.d, TF = (long)m.T * m.dff;
     const int grid = k::scatter_grid();
     const int grad_f32 = (grad_dtype == LORY_F32) ? 1 : 0;
+    // token contractions with the merge inside the GEMM (no re-merged slabs); the per-segment weight
+    // gradients still pass through the slab
+    const bool fused = !Wbar && m.S <= pl.Sc && use_fused(m);
 
     for (int s0 = 0; s0 < m.S; s0 += pl.Sc) {
         const int S = (m.S - s0 < pl.Sc) ? (m.S - s0) : pl.Sc;
@@ -321,6 +402,13 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
         if (G && U) {
             Gc = G + (size_t)s0 * TF;
             Uc = U + (size_t)s0 * TF;
+        } else if (fused) {
+            LORY_TRY(fused_gemm(st, m, prof::kFusedGU,
+                                fused_params(m, X, nullptr, m.d, Wg, nullptr, m.dff, w, m.dff, m.d, Gr, m.dff), 1, true));
+            LORY_TRY(fused_gemm(st, m, prof::kFusedGU,
+                                fused_params(m, X, nullptr, m.d, Wu, nullptr, m.dff, w, m.dff, m.d, Ur, m.dff), 1, true));
+            Gc = Gr;
+            Uc = Ur;
         } else {
             // the backward slab region holds four slabs of nf_bwd columns, i.e. a gate and an
             // up slab of 2 * nf_bwd columns each
@@ -333,6 +421,15 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
             Uc = Ur;
         }
 
+        if (fused) {
+            // dA = dY Wd_bar^T for all of d_ff at once (Wd[e] is [d_ff][d]: K contiguous), then the
+            // SwiGLU backward pass: dG, dU, A
+            LORY_TRY(fused_gemm(st, m, prof::kFusedDA,
+                                fused_params(m, dY, nullptr, m.d, Wd, nullptr, m.d, w, m.dff, m.d, dG, m.dff), 1, false));
+            prof::Range r2(st, prof::kSwigluBwd, 12.0 * m.tokens * m.dff, 2.0 * 6.0 * m.tokens * m.dff);
+            LORY_TRY(k::launch_swiglu_bwd(st, Gc, Uc, dG, dU, Act, m.tokens, m.dff, 0, m.dff));
+        }
+
         // ---- d_ff blocks: dA (+ SwiGLU backward), weight-gradient slabs, scatter
         for (int n0 = 0; n0 < m.dff; n0 += pl.nf_bwd) {
             const int nf = (m.dff - n0 < pl.nf_bwd) ? (m.dff - n0) : pl.nf_bwd;
@@ -342,8 +439,8 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
             const Rect cols_f = rect(m.D, m.dff, 0, m.d, n0, nf);    // columns n0.. of Wg/Wu [d, d_ff]
 
             // dA = dY Wd_bar^T for these d_ff columns, then the SwiGLU backward pass: dG, dU, A
-            if (!Wbar) LORY_TRY(merge(st, wc, S, m.E, Wd, rows_d, s_md));
-            {
+            if (!Wbar && !fused) LORY_TRY(merge(st, wc, S, m.E, Wd, rows_d, s_md));
+            if (!fused) {
                 Params p = {};
                 p.A[0] = dYc; p.a_batch[0] = TD; p.lda[0] = m.d;
                 p.B[0] = Wbar ? Wbar_d + (size_t)n0 * m.d : s_md;
@@ -407,8 +504,13 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
             }
         }
 
+        if (fused) {
+            // dX = dG Wg_bar^T + dU Wu_bar^T: two sources, Wg[e] / Wu[e] are [d][d_ff] (K contiguous)
+            LORY_TRY(fused_gemm(st, m, prof::kFusedDX,
+                                fused_params(m, dG, dU, m.dff, Wg, Wu, m.dff, w, m.d, m.dff, dX, m.d), 2, false));
+        }
         // ---- dX = dG Wg_bar^T + dU Wu_bar^T, one block of d columns at a time
-        for (int k0 = 0; k0 < m.d; k0 += pl.kf_bwd) {
+        for (int k0 = 0; !fused && k0 < m.d; k0 += pl.kf_bwd) {
             const int kf = (m.d - k0 < pl.kf_bwd) ? (m.d - k0) : pl.kf_bwd;
             const size_t blk = (size_t)S * kf * m.dff;
             bf *s_g = slab, *s_u = slab + blk;

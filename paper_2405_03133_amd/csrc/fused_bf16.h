@@ -1,0 +1,354 @@
+// Merge inside the GEMM: the segment's merged expert matrix (paper Eq. 2,
+// theta_bar = sum_e w[s,e] theta_e) is formed tile by tile on chip and fed
+// straight to the token contraction of Section 3.1 / Appendix B, so that no
+// merged parameter ever reaches HBM.  gfx950, bf16 operands, fp32 accumulation.
+//
+//     C[t, n] = sum over sources q, k of  A_q[t, k] * Wbar_q(seg(t))[k, n],
+//     Wbar_q(s) = sum_e w[s, e] W_q[e]
+//
+// A workgroup (4 wavefronts) owns a task: R = 4 * WROWS consecutive token rows
+// (SC = R / T whole segments) times 64 output columns, with all 65536 (WROWS =
+// 256) fp32 accumulators of the CU.  Per 16-wide K slice
+//   * every wavefront merges a quarter of the slice's 16 x 64 expert elements for
+//     all SC segments with v_mfma_f32_16x16x32_bf16 (rows = segments, K = experts,
+//     routing weights as bf16 hi + lo pairs, expert chunks transposed in registers
+//     as in the stand-alone merge kernel) and writes the bf16 result to LDS;
+//   * after one barrier every wavefront multiplies its own rows (token tiles
+//     arrive through a wave-private ring of direct global->LDS loads) with the
+//     merged tile of the segment the rows belong to.
+// Bytes entering the CU per K slice of 16: 2 * 16 * (E * 64 + R) against
+// 2 * 16 * 64 * R flops, i.e. 21 flop/byte at E = 32, R = 1024 (32 at E = 16):
+// the kernel is bound by the L2 -> CU path, not by HBM.  It does not depend on
+// the segment length except through SC, which is what makes it the better
+// choice for short segments, where the slab pipeline (merge kernel + batched
+// GEMM) moves S * d * d_ff merged values through HBM for only T rows of use each.
+#pragma once
+
+#include "gemm2_bf16.h"
+#include "merge_scatter_bf16.h"
+
+namespace lory {
+namespace fmg {
+
+using gemm::bf16x8;
+using gemm::f32x16;
+using gemm::s16x4;
+using gemm::u32x2;
+using gemm::u32x4;
+using ms::Frag;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int BN = 64;        // output columns of a task
+constexpr int BK = 32;        // K step of the token ring (two 16-wide slices)
+constexpr int kSegBytes = 2048;  // merged 16 x 64 bf16 tile of one segment
+
+struct Params {
+    const uint16_t *A[2];   // token operands [tokens][lda], K contiguous, one per source
+    int lda[2];
+    const uint16_t *W[2];   // expert stacks, one per source, already offset to the first column / row used
+    long expert_stride;     // elements between experts
+    int ldw;                // elements between rows of one expert matrix
+    const float *w;         // routing weights [S][E]
+    int E, T;
+    int tokens;             // rows of A and C
+    int N, K;               // output columns (multiple of 64); contraction length per source (multiple of 32)
+    uint16_t *C;            // [tokens][ldc]
+    int ldc;
+};
+
+template <int WROWS, int SPW>
+struct Smem {
+    static constexpr int a_stage = WROWS * 64;              // one K step of one wave's rows
+    static constexpr int a_bytes = 4 * 2 * a_stage;         // four waves, two stages
+    static constexpr int m_bytes = 4 * SPW * kSegBytes;     // one merged slice of all segments of the task
+    static constexpr int total = a_bytes + 2 * m_bytes;
+};
+
+// W_NC: expert matrices stored [K][N] (N contiguous: forward projections); else [N][K] (K contiguous:
+// the transposed uses of the backward).  SPW = WROWS / T segments per wavefront.
+template <int WROWS, int SPW, int NSRC, bool W_NC>
+__global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
+{
+    using SM = Smem<WROWS, SPW>;
+    constexpr int MI = WROWS / 32;      // 32-row blocks per wave
+    constexpr int NI = BN / 32;
+    constexpr int SC = 4 * SPW;         // segments per task
+    constexpr int R = 4 * WROWS;        // rows per task
+    constexpr int RB_SEG = MI / SPW;    // row blocks per segment
+    constexpr int NLD = WROWS / 16;     // direct loads per wave and K step
+    static_assert(SC <= 16, "the merge MFMA has 16 rows");
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    typedef __attribute__((address_space(3))) s16x4 *lds_tr_ptr;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+    char *a_ring = smem + wave * 2 * SM::a_stage;
+    const uint32_t a_ring_u = lds0 + wave_u * 2 * SM::a_stage;
+    char *m_buf = smem + SM::a_bytes;
+
+    const int c16 = lane & 15, kg = lane >> 4;   // merge roles: chunk of the unit, expert group / segment group
+    const int ksteps = p.K / BK;
+    const int G = ksteps * NSRC;                 // K steps of a task
+    const int HS = 2 * G;                        // 16-wide slices of a task
+
+    const int nrc = p.tokens / R, ncb = p.N / BN;
+    const int rcg = (nrc + 7) >> 3, cbg = (ncb + 3) >> 2;
+    const int nsuper = rcg * cbg;
+    const int xcd = blockIdx.x & 7, q0 = blockIdx.x >> 3, wg_per_xcd = gridDim.x >> 3;
+
+    // Tasks are dealt in blocks of 8 row chunks x 4 column blocks per XCD (workgroups are placed
+    // round-robin on the 8 XCDs): the 32 workgroups of an XCD then share 8 token tiles and 4 sets
+    // of expert tiles per K step in their L2, the split that minimises what the XCD fetches.
+    for (int sup = xcd; sup < nsuper; sup += 8) {
+        for (int q = q0; q < 32; q += wg_per_xcd) {
+            const int rc = (sup % rcg) * 8 + (q & 7);
+            const int cb = (sup / rcg) * 4 + (q >> 3);
+            if (rc >= nrc || cb >= ncb) continue;   // uniform over the workgroup
+
+            const int row0 = rc * R + wave * WROWS;
+            const int seg0 = (rc * R) / p.T;
+            const int n0 = cb * BN;
+
+            // ---- routing weights as the A operand of the merge MFMA: row = segment c16,
+            //      K = experts 8 kg .. 8 kg + 7; zero beyond SC segments / E experts
+            Frag whi, wlo;
+            {
+                float v[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int e = 8 * kg + i;
+                    v[i] = (c16 < SC && e < p.E) ? p.w[(size_t)(seg0 + c16) * p.E + e] : 0.f;
+                }
+                ms::split_hi_lo(v, whi, wlo);
+            }
+
+            // ---- per-lane addressing of the token ring: LDS chunk position L = 64 i + lane of the wave's
+            //      K-contiguous tile is row 16 i + lane / 4, slot lane & 3 (gemm2's swizzle, which only
+            //      depends on the low row bits, i.e. on the lane)
+            const int arow = lane >> 2;
+            const int aslot = (lane & 3) ^ gemm2::fkc(arow);
+            long a_off[NSRC];
+#pragma unroll
+            for (int s = 0; s < NSRC; ++s) a_off[s] = (long)(row0 + arow) * p.lda[s] + (aslot << 3);
+            auto issue_a = [&](int g) {
+                const int src = (NSRC == 2) ? (g / ksteps) : 0;
+                const int ks = (NSRC == 2) ? (g % ksteps) : g;
+                const uint16_t *a = p.A[src] + a_off[src] + ks * BK;
+                const long step = (long)16 * p.lda[src];
+                const uint32_t dst = a_ring_u + (g & 1) * SM::a_stage;
+#pragma unroll
+                for (int i = 0; i < NLD; ++i) gemm2::dma16(a + i * step, dst + i * 1024);
+            };
+
+            // ---- expert chunks of a slice: this wave merges units 2 wave, 2 wave + 1 (16 chunks each)
+            //      W_NC:  unit u = K rows 2u, 2u+1 x 8 chunks of 8 columns
+            //      else:  unit u = columns 8u .. 8u+7 x 2 chunks of 8 K values
+            long w_lane;   // element offset of this lane's chunk of unit 2 wave, expert group kg, slice 0
+            if constexpr (W_NC)
+                w_lane = (long)(4 * wave + (c16 >> 3)) * p.ldw + n0 + 8 * (c16 & 7);
+            else
+                w_lane = (long)(n0 + 16 * wave + (c16 >> 1)) * p.ldw + 8 * (c16 & 1);
+            const long w_unit = W_NC ? (long)2 * p.ldw : (long)8 * p.ldw;
+            long e_off[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int e = 8 * kg + i;
+                e_off[i] = (long)(e < p.E ? e : 0) * p.expert_stride;   // lanes without an expert re-read expert 0 (weight 0)
+            }
+            Frag EX[2][8];
+            auto load_ex = [&](int hs) {
+                const int g = hs >> 1;
+                const int src = (NSRC == 2) ? (g / ksteps) : 0;
+                const int ks = (NSRC == 2) ? (g % ksteps) : g;
+                const int kbase = ks * BK + (hs & 1) * 16;
+                const uint16_t *wp = p.W[src] + w_lane + (W_NC ? (long)kbase * p.ldw : (long)kbase);
+#pragma unroll
+                for (int ul = 0; ul < 2; ++ul)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        EX[ul][i].u = *reinterpret_cast<const uint4 *>(wp + ul * w_unit + e_off[i]);
+            };
+            // merged slice hs -> m_buf[hs & 1]; layout per segment
+            //   W_NC: [16 k][64 n], 32-byte granule g of row k at g ^ 2 ((k >> 1) & 1)  (read with the
+            //         transposing LDS load: four rows x 64 bytes per half wave, conflict free)
+            //   else: [64 n][16 k], 16-byte half h of row n at h ^ ((n >> 3) & 1)
+            auto produce = [&](int hs) {
+                char *mb = m_buf + (hs & 1) * SM::m_bytes;
+#pragma unroll
+                for (int ul = 0; ul < 2; ++ul) {
+                    Frag P[8];
+                    ms::transpose8x8(EX[ul], P);
+                    f32x4 macc[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        macc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        macc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(whi.v, P[j].v, macc[j], 0, 0, 0);
+                        macc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wlo.v, P[j].v, macc[j], 0, 0, 0);
+                    }
+                    int off;
+                    if constexpr (W_NC) {
+                        const int kl = 4 * wave + 2 * ul + (c16 >> 3);
+                        const int g32 = ((c16 & 7) >> 1) ^ (ul << 1);
+                        off = kl * 128 + (g32 << 5) + ((c16 & 1) << 4);
+                    } else {
+                        const int nl = 16 * wave + 8 * ul + (c16 >> 1);
+                        off = nl * 32 + (((c16 & 1) ^ ul) << 4);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int seg = 4 * kg + r;
+                        if (seg < SC) {
+                            uint4 o;
+                            o.x = ms::pack_bf16(macc[0][r], macc[1][r]);
+                            o.y = ms::pack_bf16(macc[2][r], macc[3][r]);
+                            o.z = ms::pack_bf16(macc[4][r], macc[5][r]);
+                            o.w = ms::pack_bf16(macc[6][r], macc[7][r]);
+                            *reinterpret_cast<uint4 *>(mb + seg * kSegBytes + off) = o;
+                        }
+                    }
+                }
+            };
+            // B operand of the token MFMA: columns jn * 32 .. + 31 of segment sl's merged slice
+            auto frag_b = [&](const char *mb, int sl, int jn) -> bf16x8 {
+                if constexpr (W_NC) {
+                    const int g16 = lane >> 4, r = lane & 15;
+                    const int coloff = (jn * 32 + 16 * (g16 & 1) + 4 * (r & 3)) * 2;
+                    const int krow = 8 * (g16 >> 1) + (r >> 2);
+                    const int g32 = (coloff >> 5) ^ (((krow >> 1) & 1) << 1);
+                    const char *q = mb + sl * kSegBytes + krow * 128 + (g32 << 5) + (coloff & 31);
+                    union {
+                        s16x4 h[2];
+                        bf16x8 v;
+                    } u;
+                    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_tr_ptr)(q));
+                    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_tr_ptr)(q + 4 * 128));
+                    return u.v;
+                } else {
+                    const int n = jn * 32 + (lane & 31);
+                    const int half = (lane >> 5) ^ ((n >> 3) & 1);
+                    return *reinterpret_cast<const bf16x8 *>(mb + sl * kSegBytes + n * 32 + (half << 4));
+                }
+            };
+
+            f32x16 acc[MI][NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+            // ---- prologue: token tile of K step 0 in flight, merged slice 0 produced, expert chunks
+            //      of slice 1 in flight
+            issue_a(0);
+            load_ex(0);
+            produce(0);
+            if (HS > 1) load_ex(1);
+
+            for (int hs = 0; hs < HS; ++hs) {
+                const int g = hs >> 1, h = hs & 1;
+                if (h == 0) {
+                    // Everything this wave has in flight has landed: token tile g and the expert chunks
+                    // of slice hs + 1 (needed below anyway).  LDS reads of the ring slot about to be
+                    // refilled have returned.
+                    gemm2::wait_vmcnt<0>();
+                    __builtin_amdgcn_s_waitcnt(0xC07F);
+                    if (g + 1 < G) issue_a(g + 1);
+                }
+                // merged slice hs is complete for every wave; nobody reads slice hs - 1 any more
+                gemm2::ring_barrier();
+
+                const char *as = a_ring + (g & 1) * SM::a_stage;
+                const char *mb = m_buf + (hs & 1) * SM::m_bytes;
+#pragma unroll
+                for (int sg = 0; sg < SPW; ++sg) {
+                    bf16x8 bfr[NI];
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) bfr[j] = frag_b(mb, wave * SPW + sg, j);
+#pragma unroll
+                    for (int ib = 0; ib < RB_SEG; ++ib) {
+                        const int i = sg * RB_SEG + ib;
+                        const bf16x8 af = gemm2::frag_kc(as, i * 32, h, lane);
+#pragma unroll
+                        for (int j = 0; j < NI; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af, acc[i][j], 0, 0, 0);
+                    }
+                }
+                if (hs + 1 < HS) produce(hs + 1);
+                if (hs + 2 < HS) load_ex(hs + 2);
+            }
+
+            // ---- epilogue, wave-local: 32-row blocks leave through the wave's own ring memory (all of
+            //      its direct loads have landed) as 16-byte stores, 128 bytes contiguous per row.
+            //      Accumulator element r of a block: row lane & 31, column 8 (r >> 2) + 4 (lane >> 5) + (r & 3).
+            {
+                char *stg = a_ring;
+                const int r31 = lane & 31, h2 = lane >> 5;
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+#pragma unroll
+                        for (int rq = 0; rq < 4; ++rq) {
+                            const int nl = j * 32 + 8 * rq + 4 * h2;
+                            u32x2 pk;
+                            pk.x = gemm::cvt_pk_bf16(acc[i][j][rq * 4 + 0], acc[i][j][rq * 4 + 1]);
+                            pk.y = gemm::cvt_pk_bf16(acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]);
+                            const int c = nl >> 3;
+                            *reinterpret_cast<u32x2 *>(stg + r31 * 128 + ((c ^ (r31 & 7)) << 4) + h2 * 8) = pk;
+                        }
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int it = 0; it < 4; ++it) {
+                        const int idx = it * 64 + lane;
+                        const int row = idx >> 3, c = idx & 7;
+                        const u32x4 val = *reinterpret_cast<const u32x4 *>(stg + row * 128 + ((c ^ (row & 7)) << 4));
+                        __builtin_nontemporal_store(
+                            val, reinterpret_cast<u32x4 *>(p.C + (size_t)(row0 + i * 32 + row) * p.ldc + n0 + c * 8));
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+            // the next task's prologue refills ring slot 0 and merged buffer 0: every wave is past the
+            // last barrier, after which only buffer 1 and the waves' own ring memory were read
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+        }
+    }
+    gemm2::wait_vmcnt<0>();
+}
+
+// Shapes the kernel takes: whole tasks only.
+template <int WROWS, int SPW>
+inline bool fits(const Params &p)
+{
+    return p.T * SPW == WROWS && p.tokens % (4 * WROWS) == 0 && p.N % BN == 0 && p.K % BK == 0 && p.E <= 32 &&
+           p.E >= 1;
+}
+
+template <int WROWS, int SPW, int NSRC, bool W_NC>
+inline hipError_t launch(const Params &p, hipStream_t st)
+{
+    using SM = Smem<WROWS, SPW>;
+    auto kern = fmg_kernel<WROWS, SPW, NSRC, W_NC>;
+    static bool configured = false;  // per instantiation
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, SM::total);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const long tasks = (long)(p.tokens / (4 * WROWS)) * (p.N / BN);
+    long blocks = (tasks + 7) / 8 * 8;
+    if (blocks > gemm2::persistent_grid()) blocks = gemm2::persistent_grid();
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kThreads), SM::total, st, p);
+    return hipGetLastError();
+}
+
+}  // namespace fmg
+}  // namespace lory

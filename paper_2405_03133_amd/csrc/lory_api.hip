@@ -60,6 +60,8 @@ const char *lory_version(void) { return "0.1"; }
 
 int lory_set_slab_budget(size_t bytes) { return lory::set_slab_budget(bytes); }
 
+int lory_set_fused_merge(int mode) { return lory::set_fused_mode(mode); }
+
 int lory_profile_enable(int on) { return lory::prof::set_enabled(on); }
 
 int lory_profile_read(lory_kernel_stat *out, int max_out, int *n_out)

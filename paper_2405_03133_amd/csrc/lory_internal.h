@@ -43,7 +43,7 @@ inline int launch_status()
 // ---- optional event timing per kernel class (profile.hip)
 namespace prof {
 enum Class { kRoute = 0, kMerge, kGemmGU, kSwigluFwd, kGemmDown, kGemmDA, kSwigluBwd, kGemmDX, kGemmDWGU, kGemmDWD, kScatter,
-             kDwReduce, kRouteBwd, kDenseSkinny, kNumClasses };
+             kDwReduce, kRouteBwd, kDenseSkinny, kFusedGU, kFusedDown, kFusedDA, kFusedDX, kNumClasses };
 bool enabled();
 int set_enabled(int on);
 int read(lory_kernel_stat *out, int max_out, int *n_out);
@@ -96,6 +96,7 @@ int bf16_merge_all(const Dims &m, const float *w, const void *Wg, const void *Wu
 size_t bf16_dense_workspace_bytes(const Dims &m);
 int bf16_dense_ffn_fwd(const Dims &m, const void *X, const void *Wbar, void *Y, void *ws, hipStream_t st);
 int set_slab_budget(size_t bytes);
+int set_fused_mode(int mode);
 size_t bf16_workspace_bytes(const Dims &m, int pass);
 size_t bf16_merged_save_bytes(const Dims &m);
 int bf16_ffn_fwd(const Dims &m, const void *X, const float *w, const void *Wg, const void *Wu,

@@ -243,6 +243,55 @@ def test_bf16_saved_merged_parameters_match_remerge(idx, default_budget):
         assert np.array_equal(a[key], b[key]), key
 
 
+# ------------------------------------------------------------------ merge inside the GEMM
+
+FUSED_CASES = [
+    # T = 256: one segment per wavefront; odd number of 64-column blocks, K not a multiple of 64
+    LoryConfig("fused_T256", B=2, L=1024, T=256, d=192, d_ff=320, E=8, dtype="bf16", seed=91),
+    # T = 128 on the large tile (two segments per wavefront) and on the small one (512 tokens)
+    LoryConfig("fused_T128", B=2, L=512, T=128, d=128, d_ff=192, E=32, dtype="bf16", seed=92),
+    LoryConfig("fused_T128_small", B=1, L=512, T=128, d=128, d_ff=128, E=5, dtype="bf16", seed=93),
+    # T = 64: two segments per wavefront on the small tile; three tasks along the rows
+    LoryConfig("fused_T64", B=3, L=512, T=64, d=128, d_ff=256, E=16, dtype="bf16", seed=94),
+    LoryConfig("fused_one_expert", B=1, L=1024, T=256, d=64, d_ff=64, E=1, dtype="bf16", seed=95),
+    # more tasks than one round of workgroups per XCD block, several K steps per source
+    LoryConfig("fused_many_tasks", B=4, L=2048, T=128, d=512, d_ff=1024, E=16, dtype="bf16", seed=96),
+]
+
+
+@pytest.fixture
+def fused_everywhere():
+    lb.lory_set_fused_merge(1)
+    yield
+    lb.lory_set_fused_merge(0)
+
+
+@pytest.mark.parametrize("cfg", FUSED_CASES, ids=lambda c: c.name)
+@pytest.mark.parametrize("save", [True, False], ids=["saved_GU", "recompute_GU"])
+def test_bf16_fused_merge_gemm(cfg, save, fused_everywhere, default_budget):
+    """Token contractions with the merge inside the GEMM (no merged parameter in memory), forward
+    and backward, against the oracle; and bit-reproducible."""
+    t = make_inputs(cfg, structured=True)
+    got = run_layer(cfg, t, save=save, grad_dtype=torch.bfloat16)
+    ref = oracle_layer(cfg, t, got["w_used"])
+    names = ALL if save else ("Y", "dX", "dWg", "dWu", "dWd", "dw")
+    compare(cfg, got, ref, names, TOL["bf16"])
+    again = run_layer(cfg, t, save=save, grad_dtype=torch.bfloat16)
+    for key in names:
+        assert np.array_equal(got[key], again[key]), key
+
+
+def test_bf16_fused_onehot_routing(fused_everywhere):
+    """One-hot routing weights select exactly one expert: the fused kernel's merged tiles are then
+    copies of that expert's (bf16 values pass through the hi + lo weight pair unchanged)."""
+    cfg = FUSED_CASES[3]
+    t = make_inputs(cfg)
+    w1 = make_routing_weights(cfg, "onehot")
+    got = run_layer(cfg, t, w_override=w1)
+    ref = oracle_layer(cfg, t, w1)
+    compare(cfg, got, ref, ALL, TOL["bf16"])
+
+
 def test_merged_save_unsupported_shapes_are_rejected():
     shape = lb.make_shape(5, 3840, 64, 64, 128, 64, torch.bfloat16)   # S = 300 > 128 at E = 64
     assert lb.lory_merged_save_bytes(shape) == 0
