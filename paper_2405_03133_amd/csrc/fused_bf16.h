@@ -68,7 +68,11 @@ struct Smem {
 
 // W_NC: expert matrices stored [K][N] (N contiguous: forward projections); else [N][K] (K contiguous:
 // the transposed uses of the backward).  SPW = WROWS / T segments per wavefront.
-template <int WROWS, int SPW, int NSRC, bool W_NC>
+// E16 (at most 16 experts and 8 segments per task): one merge MFMA covers both units of the wave,
+// experts of unit 0 in K 0..15 against rows 0..7, experts of unit 1 in K 16..31 against rows 8..15
+// (the routing-weight operand is block diagonal), which halves the expert loads and the merge MFMAs
+// and leaves registers for two slices of expert chunks in flight.
+template <int WROWS, int SPW, int NSRC, bool W_NC, bool E16>
 __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
 {
     using SM = Smem<WROWS, SPW>;
@@ -79,6 +83,7 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
     constexpr int RB_SEG = MI / SPW;    // row blocks per segment
     constexpr int NLD = WROWS / 16;     // direct loads per wave and K step
     static_assert(SC <= 16, "the merge MFMA has 16 rows");
+    static_assert(!E16 || SC <= 8, "two units share the 16 rows of one merge MFMA");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
     typedef __attribute__((address_space(3))) s16x4 *lds_tr_ptr;
@@ -115,15 +120,23 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
             const int seg0 = (rc * R) / p.T;
             const int n0 = cb * BN;
 
-            // ---- routing weights as the A operand of the merge MFMA: row = segment c16,
-            //      K = experts 8 kg .. 8 kg + 7; zero beyond SC segments / E experts
+            // ---- routing weights as the A operand of the merge MFMA: row = c16, K = 8 kg .. 8 kg + 7.
+            //      Plain: row = segment, K = expert.  E16: rows 0..7 = segments against K 0..15 = experts
+            //      (unit 0), rows 8..15 = the same segments against K 16..31 = experts (unit 1).
             Frag whi, wlo;
             {
                 float v[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const int e = 8 * kg + i;
-                    v[i] = (c16 < SC && e < p.E) ? p.w[(size_t)(seg0 + c16) * p.E + e] : 0.f;
+                    const int kk = 8 * kg + i;
+                    int seg = c16, e = kk;
+                    bool ok = true;
+                    if constexpr (E16) {
+                        seg = c16 & 7;
+                        e = kk & 15;
+                        ok = (c16 >> 3) == (kk >> 4);
+                    }
+                    v[i] = (ok && seg < SC && e < p.E) ? p.w[(size_t)(seg0 + seg) * p.E + e] : 0.f;
                 }
                 ms::split_hi_lo(v, whi, wlo);
             }
@@ -149,41 +162,50 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
             // ---- expert chunks of a slice: this wave merges units 2 wave, 2 wave + 1 (16 chunks each)
             //      W_NC:  unit u = K rows 2u, 2u+1 x 8 chunks of 8 columns
             //      else:  unit u = columns 8u .. 8u+7 x 2 chunks of 8 K values
-            long w_lane;   // element offset of this lane's chunk of unit 2 wave, expert group kg, slice 0
+            //      Plain: lane (c16, kg) loads chunk c16 of both units from experts 8 kg .. 8 kg + 7.
+            //      E16:   lane (c16, kg) loads chunk c16 of unit kg >> 1 from experts 8 (kg & 1) .. + 7.
+            const long w_unit = W_NC ? (long)2 * p.ldw : (long)8 * p.ldw;
+            long w_lane;   // element offset of this lane's chunk (unit 2 wave, or its own unit), slice 0, expert 0
             if constexpr (W_NC)
                 w_lane = (long)(4 * wave + (c16 >> 3)) * p.ldw + n0 + 8 * (c16 & 7);
             else
                 w_lane = (long)(n0 + 16 * wave + (c16 >> 1)) * p.ldw + 8 * (c16 & 1);
-            const long w_unit = W_NC ? (long)2 * p.ldw : (long)8 * p.ldw;
-            long e_off[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int e = 8 * kg + i;
-                e_off[i] = (long)(e < p.E ? e : 0) * p.expert_stride;   // lanes without an expert re-read expert 0 (weight 0)
+            if constexpr (E16) w_lane += (kg >> 1) * w_unit;
+            {
+                const int e0 = E16 ? 8 * (kg & 1) : 8 * kg;
+                w_lane += (long)(e0 < p.E ? e0 : 0) * p.expert_stride;   // lanes without experts re-read expert 0 (weight 0)
             }
-            Frag EX[2][8];
-            auto load_ex = [&](int hs) {
+            const int e_first = E16 ? 8 * (kg & 1) : 8 * kg;
+            constexpr int NEX = E16 ? 2 : 1;   // slices of expert chunks in flight
+            constexpr int NUL = E16 ? 1 : 2;   // load groups per slice
+            Frag EX[NEX][NUL][8];
+            auto load_ex = [&](auto buf, int hs) {
                 const int g = hs >> 1;
                 const int src = (NSRC == 2) ? (g / ksteps) : 0;
                 const int ks = (NSRC == 2) ? (g % ksteps) : g;
                 const int kbase = ks * BK + (hs & 1) * 16;
                 const uint16_t *wp = p.W[src] + w_lane + (W_NC ? (long)kbase * p.ldw : (long)kbase);
 #pragma unroll
-                for (int ul = 0; ul < 2; ++ul)
+                for (int ul = 0; ul < NUL; ++ul)
 #pragma unroll
-                    for (int i = 0; i < 8; ++i)
-                        EX[ul][i].u = *reinterpret_cast<const uint4 *>(wp + ul * w_unit + e_off[i]);
+                    for (int i = 0; i < 8; ++i) {
+                        // experts beyond E: any valid address (their routing weight is zero)
+                        const long eo = (e_first + i < p.E) ? (long)i * p.expert_stride : 0;
+                        EX[buf][ul][i].u = *reinterpret_cast<const uint4 *>(wp + ul * w_unit + eo);
+                    }
             };
             // merged slice hs -> m_buf[hs & 1]; layout per segment
             //   W_NC: [16 k][64 n], 32-byte granule g of row k at g ^ 2 ((k >> 1) & 1)  (read with the
             //         transposing LDS load: four rows x 64 bytes per half wave, conflict free)
             //   else: [64 n][16 k], 16-byte half h of row n at h ^ ((n >> 3) & 1)
-            auto produce = [&](int hs) {
+            // Output rows of the merge MFMA held by this lane: 4 kg + r.  Plain: segment 4 kg + r of the
+            // unit being processed.  E16: unit kg >> 1, segment 4 (kg & 1) + r.
+            auto produce = [&](auto buf, int hs) {
                 char *mb = m_buf + (hs & 1) * SM::m_bytes;
 #pragma unroll
-                for (int ul = 0; ul < 2; ++ul) {
+                for (int ul = 0; ul < NUL; ++ul) {
                     Frag P[8];
-                    ms::transpose8x8(EX[ul], P);
+                    ms::transpose8x8(EX[buf][ul], P);
                     f32x4 macc[8];
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
@@ -191,18 +213,20 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
                         macc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(whi.v, P[j].v, macc[j], 0, 0, 0);
                         macc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wlo.v, P[j].v, macc[j], 0, 0, 0);
                     }
+                    const int uo = E16 ? (kg >> 1) : ul;          // unit (2 wave + uo) these rows belong to
+                    const int sbase = E16 ? 4 * (kg & 1) : 4 * kg;
                     int off;
                     if constexpr (W_NC) {
-                        const int kl = 4 * wave + 2 * ul + (c16 >> 3);
-                        const int g32 = ((c16 & 7) >> 1) ^ (ul << 1);
+                        const int kl = 4 * wave + 2 * uo + (c16 >> 3);
+                        const int g32 = ((c16 & 7) >> 1) ^ (uo << 1);
                         off = kl * 128 + (g32 << 5) + ((c16 & 1) << 4);
                     } else {
-                        const int nl = 16 * wave + 8 * ul + (c16 >> 1);
-                        off = nl * 32 + (((c16 & 1) ^ ul) << 4);
+                        const int nl = 16 * wave + 8 * uo + (c16 >> 1);
+                        off = nl * 32 + (((c16 & 1) ^ uo) << 4);
                     }
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const int seg = 4 * kg + r;
+                        const int seg = sbase + r;
                         if (seg < SC) {
                             uint4 o;
                             o.x = ms::pack_bf16(macc[0][r], macc[1][r]);
@@ -244,26 +268,9 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-            // ---- prologue: token tile of K step 0 in flight, merged slice 0 produced, expert chunks
-            //      of slice 1 in flight
-            issue_a(0);
-            load_ex(0);
-            produce(0);
-            if (HS > 1) load_ex(1);
-
-            for (int hs = 0; hs < HS; ++hs) {
+            // The token MFMAs of slice hs: this wave's rows against the merged tiles of their segments.
+            auto multiply = [&](int hs) {
                 const int g = hs >> 1, h = hs & 1;
-                if (h == 0) {
-                    // Everything this wave has in flight has landed: token tile g and the expert chunks
-                    // of slice hs + 1 (needed below anyway).  LDS reads of the ring slot about to be
-                    // refilled have returned.
-                    gemm2::wait_vmcnt<0>();
-                    __builtin_amdgcn_s_waitcnt(0xC07F);
-                    if (g + 1 < G) issue_a(g + 1);
-                }
-                // merged slice hs is complete for every wave; nobody reads slice hs - 1 any more
-                gemm2::ring_barrier();
-
                 const char *as = a_ring + (g & 1) * SM::a_stage;
                 const char *mb = m_buf + (hs & 1) * SM::m_bytes;
 #pragma unroll
@@ -280,8 +287,48 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af, acc[i][j], 0, 0, 0);
                     }
                 }
-                if (hs + 1 < HS) produce(hs + 1);
-                if (hs + 2 < HS) load_ex(hs + 2);
+            };
+            using B0 = std::integral_constant<int, 0>;
+            using B1 = std::integral_constant<int, NEX - 1>;
+
+            // ---- schedule.  Slice hs is multiplied while slice hs + 1 is merged (into the other merged
+            // buffer) and the expert chunks of slice hs + 1 + NEX are fetched into the registers the
+            // merge has just freed.  Token tiles are fetched two K steps ahead, right BEFORE a group of
+            // expert loads whose data is consumed before the tile is read: loads retire in order, so
+            // the wait the compiler puts in front of that consumption also covers the tile (the direct
+            // loads themselves are invisible to its bookkeeping, which makes its waits stricter than
+            // needed, never weaker).  (Issuing the tile after the group instead measured slower: the
+            // compiler's wait for the PREVIOUS group then also has to retire half of the tile.)
+            issue_a(0);
+            if (G > 1) issue_a(1);
+            load_ex(B0(), 0);
+            if constexpr (E16) {
+                if (HS > 1) load_ex(B1(), 1);
+            }
+            gemm2::wait_vmcnt<0>();
+            produce(B0(), 0);
+            if constexpr (E16) {
+                if (HS > 2) load_ex(B0(), 2);
+            } else {
+                if (HS > 1) load_ex(B0(), 1);
+            }
+
+            for (int g = 0; g < G; ++g) {
+                const int hs = 2 * g;
+                // ---- even slice
+                gemm2::ring_barrier();   // merged slice hs complete for every wave; slice hs - 1 no longer read
+                multiply(hs);
+                produce(B1(), hs + 1);
+                if (hs + 1 + NEX < HS) load_ex(B1(), hs + 1 + NEX);
+                // ---- odd slice
+                gemm2::ring_barrier();
+                multiply(hs + 1);
+                if (hs + 2 < HS) produce(B0(), hs + 2);
+                if (g + 2 < G) {
+                    __builtin_amdgcn_s_waitcnt(0xC07F);   // this wave's reads of ring slot g & 1 have returned
+                    issue_a(g + 2);
+                }
+                if (hs + 2 + NEX < HS) load_ex(B0(), hs + 2 + NEX);
             }
 
             // ---- epilogue, wave-local: 32-row blocks leave through the wave's own ring memory (all of
@@ -331,11 +378,11 @@ inline bool fits(const Params &p)
            p.E >= 1;
 }
 
-template <int WROWS, int SPW, int NSRC, bool W_NC>
-inline hipError_t launch(const Params &p, hipStream_t st)
+template <int WROWS, int SPW, int NSRC, bool W_NC, bool E16>
+inline hipError_t launch_t(const Params &p, hipStream_t st)
 {
     using SM = Smem<WROWS, SPW>;
-    auto kern = fmg_kernel<WROWS, SPW, NSRC, W_NC>;
+    auto kern = fmg_kernel<WROWS, SPW, NSRC, W_NC, E16>;
     static bool configured = false;  // per instantiation
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -348,6 +395,15 @@ inline hipError_t launch(const Params &p, hipStream_t st)
     if (blocks > gemm2::persistent_grid()) blocks = gemm2::persistent_grid();
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kThreads), SM::total, st, p);
     return hipGetLastError();
+}
+
+template <int WROWS, int SPW, int NSRC, bool W_NC>
+inline hipError_t launch(const Params &p, hipStream_t st)
+{
+    if constexpr (4 * SPW <= 8) {
+        if (p.E <= 16) return launch_t<WROWS, SPW, NSRC, W_NC, true>(p, st);
+    }
+    return launch_t<WROWS, SPW, NSRC, W_NC, false>(p, st);
 }
 
 }  // namespace fmg
