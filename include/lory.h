@@ -85,13 +85,16 @@ const char *lory_version(void);
 int lory_set_slab_budget(size_t bytes);
 
 /*
- * Tuning knob (process-global, host-only): run the token contractions of
- * LORY_BF16 shapes with the merge INSIDE the GEMM (Eq. 2's theta_bar formed
+ * Tuning knob (process-global, host-only): which LORY_BF16 shapes run their
+ * token contractions with the merge INSIDE the GEMM (Eq. 2's theta_bar formed
  * tile by tile on chip and consumed there: no merged parameter reaches HBM, in
  * the forward or in the backward's re-merge) instead of the slab pipeline.
- *   0  never (default: the slab pipeline measured faster at every benchmark
- *      shape; the fused kernel is bound by the L2 -> CU path)
- *   1  wherever the shape fits the kernel: T in {64, 128, 256}, E <= 32,
+ *   0  never
+ *   1  where it measured faster (default): T <= 64 and E <= 16, shape fitting
+ *      the kernel.  The fused kernel is bound by the L2 -> CU path at about the
+ *      same rate for every segment length, while the slab pipeline's HBM
+ *      traffic grows with the number of segments
+ *   2  wherever the shape fits the kernel: T in {64, 128, 256}, E <= 32,
  *      B*L a multiple of 1024 (512 for T <= 128), no Wbar_save given
  * The LORY_FUSED environment variable sets the initial value.  Changes what
  * lory_workspace_bytes reports (forward pass), so set it before sizing a

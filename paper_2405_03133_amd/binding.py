@@ -138,7 +138,7 @@ def lory_set_slab_budget(nbytes: int) -> None:
 
 
 def lory_set_fused_merge(mode: int) -> None:
-    """0 = slab pipeline only (default), 1 = merge inside the GEMM wherever the shape fits the kernel."""
+    """0 = slab pipeline only, 1 = merge inside the GEMM for short segments (default), 2 = wherever it fits."""
     _check(lib().lory_set_fused_merge(int(mode)), "lory_set_fused_merge")
 
 

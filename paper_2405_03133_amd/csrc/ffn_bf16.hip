@@ -47,18 +47,19 @@ size_t slab_budget_bytes()
     return g_slab_budget;
 }
 
-// Whether the token contractions take the merge-inside-the-GEMM kernels (fused_bf16.h) instead of
-// the slab pipeline, for shapes that fit them.  Off by default: at every benchmark shape measured
-// so far the slab pipeline is faster (the fused kernel is bound by the L2 -> CU path).
+// Which shapes run their token contractions with the merge inside the GEMM (fused_bf16.h) instead
+// of the slab pipeline: 0 never, 1 where it measured faster (segments of at most 64 tokens with at
+// most 16 experts: the slab pipeline then moves four times the merged parameters of T = 256 through
+// HBM for a quarter of the rows each), 2 wherever the shape fits the kernel.
 int g_fused_mode = -1;  // -1 = not initialised yet
 
 int fused_mode()
 {
     if (g_fused_mode < 0) {
-        int mode = 0;
+        int mode = 1;
         if (const char *env = getenv("LORY_FUSED")) {
             const long v = atol(env);
-            if (v == 0 || v == 1) mode = (int)v;
+            if (v >= 0 && v <= 2) mode = (int)v;
         }
         g_fused_mode = mode;
     }
@@ -86,7 +87,8 @@ bool use_fused(const Dims &m)
                                        nullptr, m.dff);
     const fmg::Params b = fused_params(m, nullptr, nullptr, m.dff, nullptr, nullptr, m.d, nullptr, m.d, m.dff,
                                        nullptr, m.d);
-    return k::fused_fits(a) && k::fused_fits(b);
+    if (!k::fused_fits(a) || !k::fused_fits(b)) return false;
+    return mode == 2 || (m.T <= 64 && m.E <= 16);
 }
 
 // One fused contraction: C = sum over sources of A_q * Wbar_q(segment), merged on chip.
@@ -218,7 +220,7 @@ hipError_t gate_up_block(hipStream_t st, const Dims &m, int S, const bf *X, cons
 
 int set_fused_mode(int mode)
 {
-    if (mode != 0 && mode != 1) return LORY_ERR_SHAPE;
+    if (mode < 0 || mode > 2) return LORY_ERR_SHAPE;
     g_fused_mode = mode;
     return LORY_OK;
 }

@@ -58,11 +58,13 @@ struct Params {
     int ldc;
 };
 
-template <int WROWS, int SPW>
+// KG: the merged tiles are formed per K step (32 wide) instead of per slice (16 wide).
+template <int WROWS, int SPW, bool KG>
 struct Smem {
     static constexpr int a_stage = WROWS * 64;              // one K step of one wave's rows
     static constexpr int a_bytes = 4 * 2 * a_stage;         // four waves, two stages
-    static constexpr int m_bytes = 4 * SPW * kSegBytes;     // one merged slice of all segments of the task
+    static constexpr int seg_bytes = KG ? 2 * kSegBytes : kSegBytes;
+    static constexpr int m_bytes = 4 * SPW * seg_bytes;     // one merged tile of all segments of the task
     static constexpr int total = a_bytes + 2 * m_bytes;
 };
 
@@ -72,10 +74,15 @@ struct Smem {
 // experts of unit 0 in K 0..15 against rows 0..7, experts of unit 1 in K 16..31 against rows 8..15
 // (the routing-weight operand is block diagonal), which halves the expert loads and the merge MFMAs
 // and leaves registers for two slices of expert chunks in flight.
-template <int WROWS, int SPW, int NSRC, bool W_NC, bool E16>
+// KG (with E16 and K-contiguous expert matrices, where the merged tiles fit): the merge works on whole
+// K steps.  A 16-wide slice of a K-contiguous row is only 32 bytes, and fetching rows in 32-byte
+// pieces measured 2.5 times as many L2 requests per byte as the forward's 128-byte rows.
+template <int WROWS, int SPW, int NSRC, bool W_NC, bool E16, bool KG>
 __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
 {
-    using SM = Smem<WROWS, SPW>;
+    static_assert(!KG || (E16 && !W_NC), "K-step-wide merged tiles: E16, K-contiguous expert matrices");
+    using SM = Smem<WROWS, SPW, KG>;
+    constexpr int SEGB = SM::seg_bytes;
     constexpr int MI = WROWS / 32;      // 32-row blocks per wave
     constexpr int NI = BN / 32;
     constexpr int SC = 4 * SPW;         // segments per task
@@ -164,13 +171,18 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
             //      else:  unit u = columns 8u .. 8u+7 x 2 chunks of 8 K values
             //      Plain: lane (c16, kg) loads chunk c16 of both units from experts 8 kg .. 8 kg + 7.
             //      E16:   lane (c16, kg) loads chunk c16 of unit kg >> 1 from experts 8 (kg & 1) .. + 7.
-            const long w_unit = W_NC ? (long)2 * p.ldw : (long)8 * p.ldw;
+            //      KG:    per K step the wave merges its 16 columns x 32 K values in two groups of 8
+            //             columns; lane (c16, kg) loads chunk c16 & 3 (8 K values) of column
+            //             4 (kg >> 1) + (c16 >> 2) of the group: 64 contiguous bytes per column.
+            const long w_unit = KG ? (long)8 * p.ldw : W_NC ? (long)2 * p.ldw : (long)8 * p.ldw;
             long w_lane;   // element offset of this lane's chunk (unit 2 wave, or its own unit), slice 0, expert 0
-            if constexpr (W_NC)
+            if constexpr (KG)
+                w_lane = (long)(n0 + 16 * wave + 4 * (kg >> 1) + (c16 >> 2)) * p.ldw + 8 * (c16 & 3);
+            else if constexpr (W_NC)
                 w_lane = (long)(4 * wave + (c16 >> 3)) * p.ldw + n0 + 8 * (c16 & 7);
             else
                 w_lane = (long)(n0 + 16 * wave + (c16 >> 1)) * p.ldw + 8 * (c16 & 1);
-            if constexpr (E16) w_lane += (kg >> 1) * w_unit;
+            if constexpr (E16 && !KG) w_lane += (kg >> 1) * w_unit;
             {
                 const int e0 = E16 ? 8 * (kg & 1) : 8 * kg;
                 w_lane += (long)(e0 < p.E ? e0 : 0) * p.expert_stride;   // lanes without experts re-read expert 0 (weight 0)
@@ -179,12 +191,14 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
             constexpr int NEX = E16 ? 2 : 1;   // slices of expert chunks in flight
             constexpr int NUL = E16 ? 1 : 2;   // load groups per slice
             Frag EX[NEX][NUL][8];
+            // Slice hs into register set buf; KG: column group buf of K step hs.
             auto load_ex = [&](auto buf, int hs) {
-                const int g = hs >> 1;
+                const int g = KG ? hs : (hs >> 1);
                 const int src = (NSRC == 2) ? (g / ksteps) : 0;
                 const int ks = (NSRC == 2) ? (g % ksteps) : g;
-                const int kbase = ks * BK + (hs & 1) * 16;
+                const int kbase = ks * BK + (KG ? 0 : (hs & 1) * 16);
                 const uint16_t *wp = p.W[src] + w_lane + (W_NC ? (long)kbase * p.ldw : (long)kbase);
+                if constexpr (KG) wp += buf * w_unit;
 #pragma unroll
                 for (int ul = 0; ul < NUL; ++ul)
 #pragma unroll
@@ -200,6 +214,8 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
             //   else: [64 n][16 k], 16-byte half h of row n at h ^ ((n >> 3) & 1)
             // Output rows of the merge MFMA held by this lane: 4 kg + r.  Plain: segment 4 kg + r of the
             // unit being processed.  E16: unit kg >> 1, segment 4 (kg & 1) + r.
+            //   KG:   [64 n][32 k], 16-byte chunk c of row n at c ^ ((n >> 2) & 3); register set buf holds
+            //         column group buf of K step hs
             auto produce = [&](auto buf, int hs) {
                 char *mb = m_buf + (hs & 1) * SM::m_bytes;
 #pragma unroll
@@ -216,7 +232,10 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
                     const int uo = E16 ? (kg >> 1) : ul;          // unit (2 wave + uo) these rows belong to
                     const int sbase = E16 ? 4 * (kg & 1) : 4 * kg;
                     int off;
-                    if constexpr (W_NC) {
+                    if constexpr (KG) {
+                        const int nl = 16 * wave + 8 * buf + 4 * uo + (c16 >> 2);
+                        off = nl * 64 + (((c16 & 3) ^ ((nl >> 2) & 3)) << 4);
+                    } else if constexpr (W_NC) {
                         const int kl = 4 * wave + 2 * uo + (c16 >> 3);
                         const int g32 = ((c16 & 7) >> 1) ^ (uo << 1);
                         off = kl * 128 + (g32 << 5) + ((c16 & 1) << 4);
@@ -233,19 +252,23 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
                             o.y = ms::pack_bf16(macc[2][r], macc[3][r]);
                             o.z = ms::pack_bf16(macc[4][r], macc[5][r]);
                             o.w = ms::pack_bf16(macc[6][r], macc[7][r]);
-                            *reinterpret_cast<uint4 *>(mb + seg * kSegBytes + off) = o;
+                            *reinterpret_cast<uint4 *>(mb + seg * SEGB + off) = o;
                         }
                     }
                 }
             };
             // B operand of the token MFMA: columns jn * 32 .. + 31 of segment sl's merged slice
-            auto frag_b = [&](const char *mb, int sl, int jn) -> bf16x8 {
-                if constexpr (W_NC) {
+            auto frag_b = [&](const char *mb, int sl, int jn, int h) -> bf16x8 {
+                if constexpr (KG) {
+                    const int n = jn * 32 + (lane & 31);
+                    const int c = (2 * h + (lane >> 5)) ^ ((n >> 2) & 3);
+                    return *reinterpret_cast<const bf16x8 *>(mb + sl * SEGB + n * 64 + (c << 4));
+                } else if constexpr (W_NC) {
                     const int g16 = lane >> 4, r = lane & 15;
                     const int coloff = (jn * 32 + 16 * (g16 & 1) + 4 * (r & 3)) * 2;
                     const int krow = 8 * (g16 >> 1) + (r >> 2);
                     const int g32 = (coloff >> 5) ^ (((krow >> 1) & 1) << 1);
-                    const char *q = mb + sl * kSegBytes + krow * 128 + (g32 << 5) + (coloff & 31);
+                    const char *q = mb + sl * SEGB + krow * 128 + (g32 << 5) + (coloff & 31);
                     union {
                         s16x4 h[2];
                         bf16x8 v;
@@ -256,7 +279,7 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
                 } else {
                     const int n = jn * 32 + (lane & 31);
                     const int half = (lane >> 5) ^ ((n >> 3) & 1);
-                    return *reinterpret_cast<const bf16x8 *>(mb + sl * kSegBytes + n * 32 + (half << 4));
+                    return *reinterpret_cast<const bf16x8 *>(mb + sl * SEGB + n * 32 + (half << 4));
                 }
             };
 
@@ -272,12 +295,12 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
             auto multiply = [&](int hs) {
                 const int g = hs >> 1, h = hs & 1;
                 const char *as = a_ring + (g & 1) * SM::a_stage;
-                const char *mb = m_buf + (hs & 1) * SM::m_bytes;
+                const char *mb = m_buf + ((KG ? g : hs) & 1) * SM::m_bytes;
 #pragma unroll
                 for (int sg = 0; sg < SPW; ++sg) {
                     bf16x8 bfr[NI];
 #pragma unroll
-                    for (int j = 0; j < NI; ++j) bfr[j] = frag_b(mb, wave * SPW + sg, j);
+                    for (int j = 0; j < NI; ++j) bfr[j] = frag_b(mb, wave * SPW + sg, j, h);
 #pragma unroll
                     for (int ib = 0; ib < RB_SEG; ++ib) {
                         const int i = sg * RB_SEG + ib;
@@ -301,19 +324,49 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
             // compiler's wait for the PREVIOUS group then also has to retire half of the tile.)
             issue_a(0);
             if (G > 1) issue_a(1);
-            load_ex(B0(), 0);
-            if constexpr (E16) {
-                if (HS > 1) load_ex(B1(), 1);
-            }
-            gemm2::wait_vmcnt<0>();
-            produce(B0(), 0);
-            if constexpr (E16) {
-                if (HS > 2) load_ex(B0(), 2);
+            if constexpr (KG) {
+                // One barrier per K step: both slices of K step g are multiplied from merged tile g
+                // while tile g + 1 is merged from the two column groups fetched during K step g - 1.
+                load_ex(B0(), 0);
+                load_ex(B1(), 0);
+                gemm2::wait_vmcnt<0>();
+                produce(B0(), 0);
+                produce(B1(), 0);
+                if (G > 1) {
+                    load_ex(B0(), 1);
+                    load_ex(B1(), 1);
+                }
             } else {
-                if (HS > 1) load_ex(B0(), 1);
+                load_ex(B0(), 0);
+                if constexpr (E16) {
+                    if (HS > 1) load_ex(B1(), 1);
+                }
+                gemm2::wait_vmcnt<0>();
+                produce(B0(), 0);
+                if constexpr (E16) {
+                    if (HS > 2) load_ex(B0(), 2);
+                } else {
+                    if (HS > 1) load_ex(B0(), 1);
+                }
             }
 
-            for (int g = 0; g < G; ++g) {
+            for (int g = 0; KG && g < G; ++g) {
+                gemm2::ring_barrier();   // merged tile g complete for every wave; tile g - 1 no longer read
+                multiply(2 * g);
+                multiply(2 * g + 1);
+                if (g + 1 < G) {
+                    produce(B0(), g + 1);
+                    produce(B1(), g + 1);
+                }
+                if (g + 2 < G) {
+                    __builtin_amdgcn_s_waitcnt(0xC07F);   // this wave's reads of ring slot g & 1 have returned
+                    issue_a(g + 2);
+                    load_ex(B0(), g + 2);
+                    load_ex(B1(), g + 2);
+                }
+            }
+
+            for (int g = 0; !KG && g < G; ++g) {
                 const int hs = 2 * g;
                 // ---- even slice
                 gemm2::ring_barrier();   // merged slice hs complete for every wave; slice hs - 1 no longer read
@@ -378,11 +431,12 @@ inline bool fits(const Params &p)
            p.E >= 1;
 }
 
-template <int WROWS, int SPW, int NSRC, bool W_NC, bool E16>
+template <int WROWS, int SPW, int NSRC, bool W_NC, bool E16, bool KG>
 inline hipError_t launch_t(const Params &p, hipStream_t st)
 {
-    using SM = Smem<WROWS, SPW>;
-    auto kern = fmg_kernel<WROWS, SPW, NSRC, W_NC, E16>;
+    using SM = Smem<WROWS, SPW, KG>;
+    static_assert(SM::total <= 160 * 1024, "LDS of one CU");
+    auto kern = fmg_kernel<WROWS, SPW, NSRC, W_NC, E16, KG>;
     static bool configured = false;  // per instantiation
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -401,9 +455,14 @@ template <int WROWS, int SPW, int NSRC, bool W_NC>
 inline hipError_t launch(const Params &p, hipStream_t st)
 {
     if constexpr (4 * SPW <= 8) {
-        if (p.E <= 16) return launch_t<WROWS, SPW, NSRC, W_NC, true>(p, st);
+        if (p.E <= 16) {
+            if constexpr (!W_NC && Smem<WROWS, SPW, true>::total <= 160 * 1024)
+                return launch_t<WROWS, SPW, NSRC, W_NC, true, true>(p, st);
+            else
+                return launch_t<WROWS, SPW, NSRC, W_NC, true, false>(p, st);
+        }
     }
-    return launch_t<WROWS, SPW, NSRC, W_NC, false>(p, st);
+    return launch_t<WROWS, SPW, NSRC, W_NC, false, false>(p, st);
 }
 
 }  // namespace fmg

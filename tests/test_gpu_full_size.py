@@ -37,10 +37,14 @@ TOL = 1e-2
 ID_TOL = 3e-2
 
 # (configuration, mode, structured inputs); modes: "remerge" = bench.py's default launch
-# configuration (G/U saved, the backward re-merges), "saved" = merged parameters handed to the
-# backward (bench.py --merged-save), "fwd" = route + forward with nothing saved.
+# configuration (G/U saved, the backward re-merges; short segments take the merge-inside-the-GEMM
+# kernels by the library's own rule), "saved" = merged parameters handed to the backward (bench.py
+# --merged-save), "fwd" = route + forward with nothing saved, "fused" = as "remerge" with the
+# merge-inside-the-GEMM kernels forced on (bench.py --fused 2).
 CASES = [
     ("C4", "remerge", False),
+    ("C4", "fused", False),
+    ("C5_T128", "fused", True),
     ("C4", "saved", True),
     ("C2", "fwd", False),
     ("C3", "remerge", True),
@@ -72,6 +76,16 @@ def test_full_size_sampled(name, mode, structured):
     dev = {k: torch.from_numpy(v).cuda().to(torch.bfloat16).contiguous() for k, v in t.items()}
     shape = lb.make_shape(cfg.B, cfg.L, cfg.T, cfg.d, cfg.d_ff, cfg.E, torch.bfloat16)
     print("[full] running GPU route/fwd/bwd", flush=True)
+    lb.lory_set_fused_merge(2 if mode == "fused" else 1)
+    try:
+        results = _run_gpu(cfg, dev, shape, mode)
+    finally:
+        lb.lory_set_fused_merge(1)
+    w, Y, G, U, dX, dWg, dWu, dWd, dw = results
+    _compare(name, cfg, t, mode, w, Y, G, U, dX, dWg, dWu, dWd, dw)
+
+
+def _run_gpu(cfg, dev, shape, mode):
     w = lb.lory_route(dev["X"], dev["R"], cfg.T, d_ff=cfg.d_ff)
     G = U = Wbar = None
     if mode != "fwd":
@@ -82,11 +96,16 @@ def test_full_size_sampled(name, mode, structured):
         assert Wbar is not None
     Y = lb.lory_merged_ffn_fwd(dev["X"], w, dev["Wg"], dev["Wu"], dev["Wd"], cfg.T, G_save=G, U_save=U,
                                Wbar_save=Wbar)
+    dX = dWg = dWu = dWd = dw = None
     if mode != "fwd":
         dX, dWg, dWu, dWd, dw = lb.lory_merged_ffn_bwd(dev["X"], w, dev["Wg"], dev["Wu"], dev["Wd"], dev["dY"],
                                                        cfg.T, G_save=G, U_save=U, grad_dtype=torch.bfloat16,
                                                        Wbar_save=Wbar)
     torch.cuda.synchronize()
+    return w, Y, G, U, dX, dWg, dWu, dWd, dw
+
+
+def _compare(name, cfg, t, mode, w, Y, G, U, dX, dWg, dWu, dWd, dw):
     w_h = host(w)
 
     # ---- routing weights, all of them

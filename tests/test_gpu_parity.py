@@ -261,9 +261,9 @@ FUSED_CASES = [
 
 @pytest.fixture
 def fused_everywhere():
-    lb.lory_set_fused_merge(1)
+    lb.lory_set_fused_merge(2)
     yield
-    lb.lory_set_fused_merge(0)
+    lb.lory_set_fused_merge(1)
 
 
 @pytest.mark.parametrize("cfg", FUSED_CASES, ids=lambda c: c.name)
