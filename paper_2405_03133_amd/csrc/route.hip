@@ -2,49 +2,73 @@
 // segment mean -> linear router -> softmax -> shift by one segment, with the
 // first segment of every sequence routed on its own mean.
 //
-// One workgroup per segment.  The pass is HBM-bound (it reads X once); the
-// mean, the logits and the softmax are all fp32 and every reduction has a
+// One workgroup per segment, or (training shapes that return the segment
+// means) a first pass over (segment, column block) workgroups for the means
+// and a second one for the router.  The pass is HBM-bound (it reads X once);
+// the mean, the logits and the softmax are all fp32 and every reduction has a
 // fixed order, so results are deterministic.
 #include "lory_internal.h"
 
-#include <hip/hip_bf16.h>
+#include "elem_io.h"
 
 namespace lory {
 
 namespace {
+
+template <typename T> using Vec = Elem<T>;
 
 constexpr int kRouteThreads = 1024;   // 16 wavefronts
 constexpr int kColThreads = 256;      // threads along the hidden dimension
 constexpr int kRowGroups = kRouteThreads / kColThreads;
 constexpr int kMaxE = 64;
 
-template <typename T> struct Vec;
-template <> struct Vec<float> {
-    static constexpr int n = 4;
-    __device__ static void load(const float *p, float (&v)[4])
+// Router of one segment (Section 3: a linear layer, then a softmax over the E experts): logits
+// z[e] = sum_j hbar[j] * R[j][e] with thread = (e, one of 16 j-groups), eight loads in flight and
+// added in order; the 16 partial sums are added in group order by the first wavefront, which then
+// takes the max-subtracted softmax with wavefront reductions.  hbar [d] and zpart [16][64] are in
+// LDS; all 1024 threads call this; lanes tid < E of the first wavefront return the probability of
+// expert tid, everyone else 0.
+template <typename T>
+__device__ __forceinline__ float router_softmax(const float *hbar, float *zpart, const T *__restrict__ R, int d,
+                                                int E, int tid)
+{
     {
-        const float4 q = *reinterpret_cast<const float4 *>(p);
-        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-    }
-    __device__ static float one(const float *p) { return *p; }
-};
-template <> struct Vec<__hip_bfloat16> {
-    static constexpr int n = 8;
-    __device__ static void load(const __hip_bfloat16 *p, float (&v)[8])
-    {
-        const uint4 q = *reinterpret_cast<const uint4 *>(p);
-        const uint32_t r[4] = {q.x, q.y, q.z, q.w};
+        const int e = tid % 64;
+        const int jg = tid / 64;
+        float acc = 0.f;
+        if (e < E) {
+            int j = jg;
+            for (; j + 7 * 16 < d; j += 8 * 16) {
+                float r[8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[2 * i] = __uint_as_float(r[i] << 16);
-            v[2 * i + 1] = __uint_as_float(r[i] & 0xffff0000u);
+                for (int i = 0; i < 8; ++i) r[i] = Vec<T>::one(R + (size_t)(j + 16 * i) * E + e);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc += hbar[j + 16 * i] * r[i];
+            }
+            for (; j < d; j += 16) acc += hbar[j] * Vec<T>::one(R + (size_t)j * E + e);
         }
+        zpart[jg * 64 + e] = acc;
     }
-    __device__ static float one(const __hip_bfloat16 *p)
-    {
-        return __uint_as_float(((uint32_t) * reinterpret_cast<const uint16_t *>(p)) << 16);
+    __syncthreads();
+    float prob = 0.f;
+    if (tid < 64) {
+        float z = -INFINITY;
+        if (tid < E) {
+            z = 0.f;
+#pragma unroll
+            for (int g = 0; g < 16; ++g) z += zpart[g * 64 + tid];
+        }
+        float zmax = z;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, off, 64));
+        const float p = (tid < E) ? expf(z - zmax) : 0.f;
+        float denom = p;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) denom += __shfl_xor(denom, off, 64);
+        prob = p / denom;
     }
-};
+    return prob;
+}
 
 // grid = S workgroups, block = 1024 threads, dynamic LDS =
 // (d + kRowGroups * kColThreads * VEC + 16 * 64) floats.
@@ -128,42 +152,8 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restric
         __syncthreads();
     }
 
-    // ---- logits z[e] = sum_j hbar[j] * R[j][e]; thread = (e, one of 16 j-groups)
-    {
-        const int e = tid % 64;
-        const int jg = tid / 64;
-        float acc = 0.f;
-        if (e < E) {
-            int j = jg;
-            for (; j + 7 * 16 < d; j += 8 * 16) {  // eight loads in flight, added in order
-                float r[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) r[i] = Vec<T>::one(R + (size_t)(j + 16 * i) * E + e);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc += hbar[j + 16 * i] * r[i];
-            }
-            for (; j < d; j += 16) acc += hbar[j] * Vec<T>::one(R + (size_t)j * E + e);
-        }
-        zpart[jg * 64 + e] = acc;
-    }
-    __syncthreads();
-
-    // ---- softmax over the E experts by the first wavefront, then the shifted store
+    const float prob = router_softmax<T>(hbar, zpart, R, d, E, tid);
     if (tid < 64) {
-        float z = -INFINITY;
-        if (tid < E) {
-            z = 0.f;
-#pragma unroll
-            for (int g = 0; g < 16; ++g) z += zpart[g * 64 + tid];
-        }
-        float zmax = z;
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, off, 64));
-        const float p = (tid < E) ? expf(z - zmax) : 0.f;
-        float denom = p;
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) denom += __shfl_xor(denom, off, 64);
-        const float prob = p / denom;
         if (tid < E) {
             // Segment k routes segment k+1; segment 0 also routes itself.
             if (k == 0) w[(size_t)s * E + tid] = prob;
@@ -245,39 +235,8 @@ __global__ __launch_bounds__(kRouteThreads) void prompt_finish_kernel(const floa
         hbar[c] = sum * inv;
     }
     __syncthreads();
-    {
-        const int e = tid % 64, jg = tid / 64;
-        float acc = 0.f;
-        if (e < E) {
-            int j = jg;
-            for (; j + 7 * 16 < d; j += 8 * 16) {
-                float r[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) r[i] = Vec<T>::one(R + (size_t)(j + 16 * i) * E + e);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc += hbar[j + 16 * i] * r[i];
-            }
-            for (; j < d; j += 16) acc += hbar[j] * Vec<T>::one(R + (size_t)j * E + e);
-        }
-        zpart[jg * 64 + e] = acc;
-    }
-    __syncthreads();
-    if (tid < 64) {
-        float z = -INFINITY;
-        if (tid < E) {
-            z = 0.f;
-#pragma unroll
-            for (int g = 0; g < 16; ++g) z += zpart[g * 64 + tid];
-        }
-        float zmax = z;
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, off, 64));
-        const float pexp = (tid < E) ? expf(z - zmax) : 0.f;
-        float denom = pexp;
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) denom += __shfl_xor(denom, off, 64);
-        if (tid < E) w[(size_t)b * E + tid] = pexp / denom;
-    }
+    const float prob = router_softmax<T>(hbar, zpart, R, d, E, tid);
+    if (tid < E) w[(size_t)b * E + tid] = prob;
 }
 
 template <typename T>
@@ -302,6 +261,97 @@ int launch_prompt_route(const Dims &m, const void *X, const int32_t *len, const 
 size_t route_lds_bytes(int d, int vec)
 {
     return sizeof(float) * ((size_t)d + (size_t)kRowGroups * kColThreads * vec + 16 * 64);
+}
+
+// ---- training shapes with hbar requested: two stages, so that a few dozen segments still fill the
+// chip.  Stage 1: grid (segments, column blocks): every workgroup takes the mean of its 256 (bf16;
+// 128 for fp32) columns over all T rows, eight rows per thread in flight, and writes it to hbar.
+// Stage 2: one workgroup per segment reads its hbar row back and routes.
+constexpr int kMeanRowGroups = 8;
+
+template <typename T>
+__global__ __launch_bounds__(256) void route_mean_kernel(const T *__restrict__ X, float *__restrict__ hbar_out,
+                                                         int Tseg, int d)
+{
+    constexpr int VEC = Vec<T>::n;
+    constexpr int COLS = 256 / kMeanRowGroups;   // column threads
+    __shared__ float part[kMeanRowGroups][COLS * VEC];
+    const int s = blockIdx.x;
+    const int tx = threadIdx.x % COLS, ty = threadIdx.x / COLS;
+    const int c = (blockIdx.y * COLS + tx) * VEC;
+    const T *Xs = X + (size_t)s * Tseg * d;
+    float acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+    if (c < d) {
+        int t = ty;
+        for (; t + 7 * kMeanRowGroups < Tseg; t += 8 * kMeanRowGroups) {  // eight rows in flight, added in row order
+            float v[8][VEC];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) Vec<T>::load(Xs + (size_t)(t + u * kMeanRowGroups) * d + c, v[u]);
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] += v[u][i];
+        }
+        for (; t < Tseg; t += kMeanRowGroups) {
+            float v[VEC];
+            Vec<T>::load(Xs + (size_t)t * d + c, v);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] += v[i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) part[ty][tx * VEC + i] = acc[i];
+    __syncthreads();
+    if (ty == 0 && c < d) {
+        const float invT = 1.0f / (float)Tseg;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            float sum = 0.f;
+#pragma unroll
+            for (int g = 0; g < kMeanRowGroups; ++g) sum += part[g][tx * VEC + i];
+            hbar_out[(size_t)s * d + c + i] = sum * invT;
+        }
+    }
+}
+
+// grid = segments, block = 1024, dynamic LDS = (d + 16 * 64) floats.
+template <typename T>
+__global__ __launch_bounds__(kRouteThreads) void route_finish_kernel(const float *__restrict__ hbar_in,
+                                                                     const T *__restrict__ R,
+                                                                     float *__restrict__ w, int d, int E, int N)
+{
+    extern __shared__ float lds[];
+    float *hbar = lds;         // [d]
+    float *zpart = lds + d;    // [16][64]
+    const int s = blockIdx.x, k = s % N, tid = threadIdx.x;
+    for (int c = tid; c < d; c += kRouteThreads) hbar[c] = hbar_in[(size_t)s * d + c];
+    __syncthreads();
+    const float prob = router_softmax<T>(hbar, zpart, R, d, E, tid);
+    if (tid < E) {
+        // Segment k routes segment k+1; segment 0 also routes itself.
+        if (k == 0) w[(size_t)s * E + tid] = prob;
+        if (k + 1 < N) w[(size_t)(s + 1) * E + tid] = prob;
+    }
+}
+
+template <typename T>
+int launch_route_two_stage(const Dims &m, const void *X, const void *R, float *w, float *hbar, hipStream_t st)
+{
+    constexpr int cols = (256 / kMeanRowGroups) * Vec<T>::n;
+    hipLaunchKernelGGL((route_mean_kernel<T>), dim3(m.S, (m.d + cols - 1) / cols), dim3(256), 0, st, (const T *)X,
+                       hbar, m.T, m.d);
+    if (hipGetLastError() != hipSuccess) return LORY_ERR_DEVICE;
+    const size_t lds = sizeof(float) * ((size_t)m.d + 16 * 64);
+    if (lds > 48 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&route_finish_kernel<T>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return LORY_ERR_DEVICE;
+    }
+    hipLaunchKernelGGL((route_finish_kernel<T>), dim3(m.S), dim3(kRouteThreads), lds, st, hbar, (const T *)R, w, m.d,
+                       m.E, m.N);
+    return launch_status();
 }
 
 template <typename T, bool VECTOR>
@@ -340,6 +390,13 @@ int route_launch(const Dims &m, const void *X, const void *R, float *w, float *h
                  hipStream_t st)
 {
     static_assert(kMaxE == 64, "logit stage assumes E <= 64");
+    // The segment means double as the exchange buffer of the two-stage path; it pays when one
+    // workgroup per segment would leave most of the chip idle.
+    if (hbar && !seg_len && m.S < 512 && m.T >= 32) {
+        if (m.dtype == LORY_F32 && m.d % Vec<float>::n == 0) return launch_route_two_stage<float>(m, X, R, w, hbar, st);
+        if (m.dtype == LORY_BF16 && m.d % Vec<__hip_bfloat16>::n == 0)
+            return launch_route_two_stage<__hip_bfloat16>(m, X, R, w, hbar, st);
+    }
     if (m.dtype == LORY_F32) {
         if (m.d % Vec<float>::n == 0) return launch_route<float, true>(m, X, R, w, hbar, seg_len, st);
         return launch_route<float, false>(m, X, R, w, hbar, seg_len, st);
