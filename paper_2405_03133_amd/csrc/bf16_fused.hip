@@ -11,6 +11,9 @@ template <int NSRC, bool W_NC>
 hipError_t launch_fused_t(hipStream_t st, const fmg::Params &p)
 {
     // segments per task are limited by the merged tiles that fit beside the token ring in LDS
+    // short segments with at most 16 experts: eight waves, two per SIMD (measured 10-25 % faster there;
+    // from T = 128 on the larger tasks of the four-wave kernel win)
+    if (fmg::fits8<64>(p)) return fmg::launch8<64, NSRC, W_NC>(p, st);
     if (fmg::fits<256, 1>(p)) return fmg::launch<256, 1, NSRC, W_NC>(p, st);   // T = 256
     if (fmg::fits<256, 2>(p)) return fmg::launch<256, 2, NSRC, W_NC>(p, st);   // T = 128
     if (fmg::fits<128, 1>(p)) return fmg::launch<128, 1, NSRC, W_NC>(p, st);   // T = 128, fewer tokens

@@ -423,11 +423,293 @@ __global__ __launch_bounds__(kThreads, 1) void fmg_kernel(const Params p)
     gemm2::wait_vmcnt<0>();
 }
 
-// Shapes the kernel takes: whole tasks only.
+// ---------------------------------------------------------------------------------------------
+// Eight-wavefront variant for at most 16 experts: 512 token rows x 64 columns per task, 64 rows and
+// 64 accumulator registers per wave, so that two waves share a SIMD and one wave's loads, LDS traffic
+// and transposes overlap the other's MFMAs (the four-wave kernel above is alone on its SIMD).
+// The merge works on whole K steps (32 wide): per K step every wave merges two 16-chunk units
+// (one load group of 8 x 16 bytes per lane, one 16x16x32 MFMA pass with the block-diagonal
+// routing-weight operand) for all R / T <= 8 segments of the task; one barrier per K step, two
+// multiplied slices between barriers.  Merged tile of a segment: 4 KB,
+//   W_NC: [32 k][64 n], 32-byte granule g of row k at g ^ 2 ((k >> 1) & 1)
+//   else: [64 n][32 k], 16-byte chunk c of row n at c ^ ((n >> 2) & 3).
+template <int TSEG>
+struct Smem8 {
+    static constexpr int a_stage = 64 * 64;                  // one K step of one wave's 64 rows
+    static constexpr int a_bytes = 8 * 2 * a_stage;          // eight waves, two stages
+    static constexpr int seg_bytes = 4096;
+    static constexpr int m_bytes = (512 / TSEG) * seg_bytes; // one merged K step of all segments of the task
+    static constexpr int total = a_bytes + 2 * m_bytes;
+};
+
+template <int TSEG, int NSRC, bool W_NC>
+__global__ __launch_bounds__(512, 1) void fmg8_kernel(const Params p)
+{
+    using SM = Smem8<TSEG>;
+    constexpr int WROWS = 64, R = 512, MI = 2, NI = 2, NLD = 4;
+    constexpr int SC = R / TSEG;
+    constexpr int SEGB = SM::seg_bytes;
+    static_assert(SC >= 1 && SC <= 8, "two units share the 16 rows of one merge MFMA");
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    typedef __attribute__((address_space(3))) s16x4 *lds_tr_ptr;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+    char *a_ring = smem + wave * 2 * SM::a_stage;
+    const uint32_t a_ring_u = lds0 + wave_u * 2 * SM::a_stage;
+    char *m_buf = smem + SM::a_bytes;
+
+    const int c16 = lane & 15, kg = lane >> 4;
+    const int ksteps = p.K / BK;
+    const int G = ksteps * NSRC;
+
+    const int nrc = p.tokens / R, ncb = p.N / BN;
+    const int rcg = (nrc + 7) >> 3, cbg = (ncb + 3) >> 2;
+    const int nsuper = rcg * cbg;
+    const int xcd = blockIdx.x & 7, q0 = blockIdx.x >> 3, wg_per_xcd = gridDim.x >> 3;
+
+    // same dealing of tasks as the four-wave kernel: 8 row chunks x 4 column blocks per XCD at a time
+    for (int sup = xcd; sup < nsuper; sup += 8) {
+        for (int q = q0; q < 32; q += wg_per_xcd) {
+            const int rc = (sup % rcg) * 8 + (q & 7);
+            const int cb = (sup / rcg) * 4 + (q >> 3);
+            if (rc >= nrc || cb >= ncb) continue;   // uniform over the workgroup
+
+            const int row0 = rc * R + wave * WROWS;
+            const int seg0 = (rc * R) / TSEG;
+            const int sl = (wave * WROWS) / TSEG;    // segment (within the task) of this wave's rows
+            const int n0 = cb * BN;
+
+            // block-diagonal routing-weight operand: rows 0..7 = segments against K 0..15 = experts
+            // (first unit), rows 8..15 = the same segments against K 16..31 = experts (second unit)
+            Frag whi, wlo;
+            {
+                float v[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int kk = 8 * kg + i;
+                    const int seg = c16 & 7, e = kk & 15;
+                    const bool ok = (c16 >> 3) == (kk >> 4);
+                    v[i] = (ok && seg < SC && e < p.E) ? p.w[(size_t)(seg0 + seg) * p.E + e] : 0.f;
+                }
+                ms::split_hi_lo(v, whi, wlo);
+            }
+
+            const int arow = lane >> 2;
+            const int aslot = (lane & 3) ^ gemm2::fkc(arow);
+            long a_off[NSRC];
+#pragma unroll
+            for (int s = 0; s < NSRC; ++s) a_off[s] = (long)(row0 + arow) * p.lda[s] + (aslot << 3);
+            auto issue_a = [&](int g) {
+                const int src = (NSRC == 2) ? (g / ksteps) : 0;
+                const int ks = (NSRC == 2) ? (g % ksteps) : g;
+                const uint16_t *a = p.A[src] + a_off[src] + ks * BK;
+                const long step = (long)16 * p.lda[src];
+                const uint32_t dst = a_ring_u + (g & 1) * SM::a_stage;
+#pragma unroll
+                for (int i = 0; i < NLD; ++i) gemm2::dma16(a + i * step, dst + i * 1024);
+            };
+
+            // expert chunks of a K step: lane (c16, kg) loads its chunk of unit kg >> 1 from experts
+            // 8 (kg & 1) .. + 7.   W_NC: units = K rows 4 wave + 2 u + {0, 1}, chunk = 8 columns.
+            // else: units = columns 8 wave + 4 u + {0..3}, chunk = 8 K values (64 bytes per column).
+            // (byte offsets from the K step's first element, 32 bits: the stack is smaller than 2 GiB)
+            uint32_t w_lane;
+            if constexpr (W_NC)
+                w_lane = (uint32_t)(4 * wave + 2 * (kg >> 1) + (c16 >> 3)) * (uint32_t)p.ldw + n0 + 8 * (c16 & 7);
+            else
+                w_lane = (uint32_t)(n0 + 8 * wave + 4 * (kg >> 1) + (c16 >> 2)) * (uint32_t)p.ldw + 8 * (c16 & 3);
+            const int e_first = 8 * (kg & 1);
+            const uint32_t stride_b = (uint32_t)p.expert_stride * 2u;
+            w_lane = w_lane * 2u + (uint32_t)(e_first < p.E ? e_first : 0) * stride_b;
+            Frag EX[8];
+            auto load_ex = [&](int g) {
+                const int src = (NSRC == 2) ? (g / ksteps) : 0;
+                const int ks = (NSRC == 2) ? (g % ksteps) : g;
+                const char *wk = reinterpret_cast<const char *>(p.W[src]) +
+                                 (W_NC ? (size_t)ks * BK * p.ldw : (size_t)ks * BK) * 2;   // wave-uniform
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t off = w_lane + ((e_first + i < p.E) ? (uint32_t)i * stride_b : 0u);   // beyond E: weight 0
+                    EX[i].u = *reinterpret_cast<const uint4 *>(wk + off);
+                }
+            };
+            auto produce = [&](int g) {
+                char *mb = m_buf + (g & 1) * SM::m_bytes;
+                Frag P[8];
+                ms::transpose8x8(EX, P);
+                const int uo = kg >> 1, sbase = 4 * (kg & 1);   // rows 4 kg + r: unit, segment
+                int off;
+                if constexpr (W_NC) {
+                    const int kl = 4 * wave + 2 * uo + (c16 >> 3);
+                    const int g32 = ((c16 & 7) >> 1) ^ (uo << 1);
+                    off = kl * 128 + (g32 << 5) + ((c16 & 1) << 4);
+                } else {
+                    const int nl = 8 * wave + 4 * uo + (c16 >> 2);
+                    off = nl * 64 + (((c16 & 3) ^ ((nl >> 2) & 3)) << 4);
+                }
+                // two halves of the 8 elements of a chunk, to keep fewer merge accumulators alive
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf) {
+                    f32x4 macc[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        macc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        macc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(whi.v, P[4 * hf + j].v, macc[j], 0, 0, 0);
+                        macc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wlo.v, P[4 * hf + j].v, macc[j], 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int seg = sbase + r;
+                        if (seg < SC) {
+                            uint2 o;
+                            o.x = ms::pack_bf16(macc[0][r], macc[1][r]);
+                            o.y = ms::pack_bf16(macc[2][r], macc[3][r]);
+                            *reinterpret_cast<uint2 *>(mb + seg * SEGB + off + 8 * hf) = o;
+                        }
+                    }
+                }
+            };
+            auto frag_b = [&](const char *mb, int jn, int h) -> bf16x8 {
+                if constexpr (W_NC) {
+                    const int g16 = lane >> 4, r = lane & 15;
+                    const int coloff = (jn * 32 + 16 * (g16 & 1) + 4 * (r & 3)) * 2;
+                    const int krow = 16 * h + 8 * (g16 >> 1) + (r >> 2);
+                    const int g32 = (coloff >> 5) ^ (((krow >> 1) & 1) << 1);
+                    const char *q = mb + sl * SEGB + krow * 128 + (g32 << 5) + (coloff & 31);
+                    union {
+                        s16x4 hh[2];
+                        bf16x8 v;
+                    } u;
+                    u.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_tr_ptr)(q));
+                    u.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_tr_ptr)(q + 4 * 128));
+                    return u.v;
+                } else {
+                    const int n = jn * 32 + (lane & 31);
+                    const int c = (2 * h + (lane >> 5)) ^ ((n >> 2) & 3);
+                    return *reinterpret_cast<const bf16x8 *>(mb + sl * SEGB + n * 64 + (c << 4));
+                }
+            };
+
+            f32x16 acc[MI][NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+            auto multiply = [&](int g, int h) {
+                const char *as = a_ring + (g & 1) * SM::a_stage;
+                const char *mb = m_buf + (g & 1) * SM::m_bytes;
+                bf16x8 bfr[NI];
+#pragma unroll
+                for (int j = 0; j < NI; ++j) bfr[j] = frag_b(mb, j, h);
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+                    const bf16x8 af = gemm2::frag_kc(as, i * 32, h, lane);
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af, acc[i][j], 0, 0, 0);
+                }
+            };
+
+            // Token tiles two K steps ahead, issued right before the expert loads of the same K step,
+            // whose data is consumed (by produce) before the tile is read: the compiler's wait in
+            // front of that consumption covers the tile (loads retire in order).  (Expert chunks two
+            // K steps ahead and a third ring stage measured the same: the kernel is bound by the bytes
+            // entering the CU, not by their latency.)
+            issue_a(0);
+            issue_a(1);
+            load_ex(0);
+            gemm2::wait_vmcnt<0>();
+            produce(0);
+            load_ex(1);
+            for (int g = 0; g < G; ++g) {   // G is even and at least 2
+                gemm2::ring_barrier();   // merged tile g complete for every wave; tile g - 1 no longer read
+                multiply(g, 0);
+                multiply(g, 1);
+                if (g + 1 < G) produce(g + 1);
+                if (g + 2 < G) {
+                    __builtin_amdgcn_s_waitcnt(0xC07F);   // this wave's reads of ring slot g & 1 have returned
+                    issue_a(g + 2);
+                    load_ex(g + 2);
+                }
+            }
+
+            // epilogue through the wave's own ring memory, as in the four-wave kernel
+            {
+                char *stg = a_ring;
+                const int r31 = lane & 31, h2 = lane >> 5;
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+#pragma unroll
+                        for (int rq = 0; rq < 4; ++rq) {
+                            const int nl = j * 32 + 8 * rq + 4 * h2;
+                            u32x2 pk;
+                            pk.x = gemm::cvt_pk_bf16(acc[i][j][rq * 4 + 0], acc[i][j][rq * 4 + 1]);
+                            pk.y = gemm::cvt_pk_bf16(acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]);
+                            const int c = nl >> 3;
+                            *reinterpret_cast<u32x2 *>(stg + r31 * 128 + ((c ^ (r31 & 7)) << 4) + h2 * 8) = pk;
+                        }
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int it = 0; it < 4; ++it) {
+                        const int idx = it * 64 + lane;
+                        const int row = idx >> 3, c = idx & 7;
+                        const u32x4 val = *reinterpret_cast<const u32x4 *>(stg + row * 128 + ((c ^ (row & 7)) << 4));
+                        __builtin_nontemporal_store(
+                            val, reinterpret_cast<u32x4 *>(p.C + (size_t)(row0 + i * 32 + row) * p.ldc + n0 + c * 8));
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+        }
+    }
+    gemm2::wait_vmcnt<0>();
+}
+
+// whole tasks and an even number of K steps, as for the four-wave kernel
+template <int TSEG>
+inline bool fits8(const Params &p)
+{
+    return p.T == TSEG && p.tokens % 512 == 0 && p.N % BN == 0 && p.K % (2 * BK) == 0 && p.E <= 16 && p.E >= 1 &&
+           (size_t)p.E * (size_t)p.expert_stride * 2 < ((size_t)1 << 31);
+}
+
+template <int TSEG, int NSRC, bool W_NC>
+inline hipError_t launch8(const Params &p, hipStream_t st)
+{
+    using SM = Smem8<TSEG>;
+    static_assert(SM::total <= 160 * 1024, "LDS of one CU");
+    auto kern = fmg8_kernel<TSEG, NSRC, W_NC>;
+    static bool configured = false;  // per instantiation
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, SM::total);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const long tasks = (long)(p.tokens / 512) * (p.N / BN);
+    long blocks = (tasks + 7) / 8 * 8;
+    if (blocks > gemm2::persistent_grid()) blocks = gemm2::persistent_grid();
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(512), SM::total, st, p);
+    return hipGetLastError();
+}
+
+// Shapes the kernel takes: whole tasks only, and an even number of K steps (a task's last merged tile
+// then sits in buffer 1, which the next task's prologue leaves alone).
 template <int WROWS, int SPW>
 inline bool fits(const Params &p)
 {
-    return p.T * SPW == WROWS && p.tokens % (4 * WROWS) == 0 && p.N % BN == 0 && p.K % BK == 0 && p.E <= 32 &&
+    return p.T * SPW == WROWS && p.tokens % (4 * WROWS) == 0 && p.N % BN == 0 && p.K % (2 * BK) == 0 && p.E <= 32 &&
            p.E >= 1;
 }
 

@@ -253,6 +253,11 @@ FUSED_CASES = [
     LoryConfig("fused_T128_small", B=1, L=512, T=128, d=128, d_ff=128, E=5, dtype="bf16", seed=93),
     # T = 64: two segments per wavefront on the small tile; three tasks along the rows
     LoryConfig("fused_T64", B=3, L=512, T=64, d=128, d_ff=256, E=16, dtype="bf16", seed=94),
+    # T = 64 on the eight-wave kernel with the second group of eight experts partly and wholly absent
+    LoryConfig("fused_T64_E11", B=2, L=256, T=64, d=128, d_ff=192, E=11, dtype="bf16", seed=97),
+    LoryConfig("fused_T64_E5", B=1, L=512, T=64, d=64, d_ff=128, E=5, dtype="bf16", seed=98),
+    # T = 64 with more than 16 experts: the four-wave kernel, two segments per wavefront
+    LoryConfig("fused_T64_E32", B=1, L=512, T=64, d=64, d_ff=128, E=32, dtype="bf16", seed=99),
     LoryConfig("fused_one_expert", B=1, L=1024, T=256, d=64, d_ff=64, E=1, dtype="bf16", seed=95),
     # more tasks than one round of workgroups per XCD block, several K steps per source
     LoryConfig("fused_many_tasks", B=4, L=2048, T=128, d=512, d_ff=1024, E=16, dtype="bf16", seed=96),
