@@ -8,6 +8,7 @@ from __future__ import annotations
 
 import glob
 import os
+import re
 import subprocess
 import sys
 
@@ -35,19 +36,42 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+RESOURCES = os.path.join(HERE, "_build", "kernel_resources.txt")
+_REMARK = re.compile(r"remark:\s+(Function Name|VGPRs|AGPRs|ScratchSize \[bytes/lane\]|LDS Size \[bytes/block\]): (\S+)")
+
+
 def _run(cmd, verbose):
+    """Run one compiler command; returns the kernels' resource usage it reported:
+    [(name, vgprs, agprs, scratch bytes per lane, static LDS bytes)]."""
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(ln for ln in proc.stdout.splitlines() if "packed-fp32-ops" not in ln)
+    kernels, other = [], []
+    for ln in proc.stdout.splitlines():
+        m = _REMARK.search(ln)
+        if m:
+            key, val = m.group(1), m.group(2)
+            if key == "Function Name":
+                kernels.append({"name": val})
+            elif kernels:
+                kernels[-1][key.split(" ")[0]] = int(val)
+        elif "packed-fp32-ops" not in ln and "-Rpass-analysis" not in ln and not re.match(r"^\s*(\d+ \|.*|\|\s*\^)\s*$", ln):
+            other.append(ln)
+    out = "\n".join(other)
     if verbose and out.strip():
         print(out)
     if proc.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
+    return [(k["name"], k.get("VGPRs", -1), k.get("AGPRs", -1), k.get("ScratchSize", -1), k.get("LDS", -1))
+            for k in kernels]
 
 
 def build(verbose: bool = True, jobs: int = 8) -> str:
-    """Compile every csrc/*.hip to an object (in parallel) and link liblory.so."""
+    """Compile every csrc/*.hip to an object (in parallel) and link liblory.so.
+
+    The compiler's per-kernel resource report goes to _build/kernel_resources.txt, and the build
+    fails if any kernel needs scratch memory (spilled registers): the kernels that count their own
+    outstanding memory operations are written for code without spills."""
     from concurrent.futures import ThreadPoolExecutor
 
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -59,9 +83,17 @@ def build(verbose: bool = True, jobs: int = 8) -> str:
     for src in sources():
         obj = os.path.join(objdir, os.path.basename(src)[:-4] + ".o")
         objs.append(obj)
-        cmds.append([hipcc] + flags + ["-c", src, "-o", obj])
+        cmds.append([hipcc] + flags + ["-Rpass-analysis=kernel-resource-usage", "-c", src, "-o", obj])
     with ThreadPoolExecutor(max_workers=jobs) as pool:
-        list(pool.map(lambda c: _run(c, verbose), cmds))
+        reports = list(pool.map(lambda c: _run(c, verbose), cmds))
+    kernels = sorted(k for rep in reports for k in rep)
+    with open(RESOURCES, "w") as f:
+        f.write("# kernel  VGPRs  AGPRs  scratch_bytes_per_lane  static_LDS_bytes\n")
+        for k in kernels:
+            f.write("%s %d %d %d %d\n" % k)
+    spilling = [k for k in kernels if k[3] != 0]
+    if spilling or not kernels:
+        raise RuntimeError("kernels that need scratch memory (or no resource report at all): %r" % spilling)
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc"] + objs + ["-o", LIB], verbose)
     return LIB
 

@@ -39,6 +39,22 @@ __device__ __forceinline__ void unpack4(u32x2 p, float (&f)[4])
 template <bool SAVE, bool ACT>
 struct EpiGUT {
     static constexpr int NOUT = 3;
+    // The ring GEMM forms the activation alone from the bf16 values of both operand sets
+    // (combine) instead of calling pack() on the accumulators.
+    static constexpr bool COMBINE = ACT && !SAVE;
+    static constexpr int COMBINED_PLANE = 0;
+    __device__ __forceinline__ gemm::u32x4 combine(gemm::u32x4 g, gemm::u32x4 u) const
+    {
+        gemm::u32x4 r;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float g0 = __uint_as_float(g[w] << 16), g1 = __uint_as_float(g[w] & 0xffff0000u);
+            const float u0 = __uint_as_float(u[w] << 16), u1 = __uint_as_float(u[w] & 0xffff0000u);
+            r[w] = gemm::cvt_pk_bf16(g0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)) * u0,
+                                     g1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)) * u1);
+        }
+        return r;
+    }
     static constexpr bool HAS_IN = false;
     typedef NoIn In;
     uint16_t *G, *U, *Act;  // [tokens, d_ff]
@@ -70,6 +86,7 @@ struct EpiGU {
 // C[batch][m][n] = bf16(v)
 struct EpiStore {
     static constexpr int NOUT = 1;
+    static constexpr bool COMBINE = false;
     static constexpr bool HAS_IN = false;
     typedef NoIn In;
     uint16_t *C;
@@ -89,6 +106,7 @@ struct EpiStore {
 
 struct EpiStore2 {
     static constexpr int NOUT = 2;
+    static constexpr bool COMBINE = false;
     static constexpr bool HAS_IN = false;
     typedef NoIn In;
     uint16_t *C0, *C1;

@@ -41,8 +41,9 @@ struct Smem {
     static constexpr int BN = 256;  // columns of the tile over all operand sets
     static constexpr int BNS = BN / NSET;
     static constexpr int ring = kStages * kStageBytes;
-    // epilogue staging: every wave owns 32 rows x (BNS / 2) columns of bf16, no padding
-    static constexpr int stage_out = 32 * (BNS / 2) * 2;
+    // epilogue staging: every wave owns 32 rows x 128 columns of bf16 (one plane of 128 columns, or
+    // the two 64-column planes of a combining epilogue), no padding
+    static constexpr int stage_out = 32 * 128 * 2;
     static constexpr int total = ring + 4 * stage_out;
 };
 
@@ -348,6 +349,40 @@ __global__ __launch_bounds__(kThreads, 1) void gemm2_kernel(const Params p, cons
         const int r = lane & 31, h = lane >> 5;
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
+            if constexpr (Epi::COMBINE) {
+                // One output plane computed from both operand sets: both are staged as bf16 and
+                // combined on the way out.  (Combined straight from the accumulators, the compiler
+                // copied the whole second set to VGPRs at the top of the epilogue and spilled.)
+                static_assert(NSET == 2, "a combining epilogue has two operand sets");
+                constexpr int PLB = 32 * WN * 2;
+#pragma unroll
+                for (int s = 0; s < NSET; ++s)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+#pragma unroll
+                        for (int rq = 0; rq < 4; ++rq) {
+                            const int c = (j * 32 + 8 * rq) >> 3;
+                            u32x2 pk;
+                            pk.x = gemm::cvt_pk_bf16(acc[s][i][j][rq * 4 + 0], acc[s][i][j][rq * 4 + 1]);
+                            pk.y = gemm::cvt_pk_bf16(acc[s][i][j][rq * 4 + 2], acc[s][i][j][rq * 4 + 3]);
+                            *reinterpret_cast<u32x2 *>(stg + s * PLB + r * (WN * 2) + ((c ^ (r & (CP - 1))) << 4) + h * 8) = pk;
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int it = 0; it < (32 * CP) / 64; ++it) {
+                    const int idx = it * 64 + lane;
+                    const int row = idx / CP, c = idx % CP;
+                    const int off = row * (WN * 2) + ((c ^ (row & (CP - 1))) << 4);
+                    const u32x4 v0 = *reinterpret_cast<const u32x4 *>(stg + off);
+                    const u32x4 v1 = *reinterpret_cast<const u32x4 *>(stg + PLB + off);
+                    __builtin_nontemporal_store(
+                        epi.combine(v0, v1),
+                        reinterpret_cast<u32x4 *>(epi.ptr(Epi::COMBINED_PLANE, batch, m0 + wm0 + i * 32 + row, n0 + wn0 + c * 8)));
+                }
+                __builtin_amdgcn_wave_barrier();
+                continue;
+            }
             // all planes of one 32-row block before the next block: its accumulators are read
             // into registers once
 #pragma unroll

@@ -147,43 +147,64 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeParams p)
             }
     };
 
+    // Up to 32 experts the next unit is fetched behind the MFMAs of the current one; with more, the
+    // registers of a second set of chunks do not exist (the kernel would spill), so a unit is
+    // fetched when its turn comes.
+    constexpr bool kPrefetch = KS <= 2;
     int unit = blockIdx.x * 4 + wave;
-    if (unit < units) load_unit(unit);
+    if (kPrefetch && unit < units) load_unit(unit);
     for (; unit < units; unit += stride) {
+        if constexpr (!kPrefetch) load_unit(unit);
         Frag P[KS][8];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) transpose8x8(R[ks], P[ks]);
-        if (unit + stride < units) load_unit(unit + stride);  // prefetch behind the MFMAs
+        if constexpr (kPrefetch) {
+            if (unit + stride < units) load_unit(unit + stride);
+        }
 
         const int q = unit * 32 + ln;
+        // JH column elements of a chunk at a time: all 8 (16-byte stores), or 4 (8-byte stores) when the
+        // chunks of more than 32 experts leave too few registers for 8 accumulator blocks
+        constexpr int JH = kPrefetch ? 8 : 4;
         for (int mb = 0; mb < MB; ++mb) {
-            f32x16 acc[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
+            for (int j0 = 0; j0 < 8; j0 += JH) {
+                f32x16 acc[JH];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+                for (int j = 0; j < JH; ++j)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                Frag whi, wlo;
-                whi.u = wtab[((mb * KS + ks) * 2 + 0) * 64 + lane];
-                wlo.u = wtab[((mb * KS + ks) * 2 + 1) * 64 + lane];
+                    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(whi.v, P[ks][j].v, acc[j], 0, 0, 0);
-                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wlo.v, P[ks][j].v, acc[j], 0, 0, 0);
+                for (int ks = 0; ks < KS; ++ks) {
+                    Frag whi, wlo;
+                    whi.u = wtab[((mb * KS + ks) * 2 + 0) * 64 + lane];
+                    wlo.u = wtab[((mb * KS + ks) * 2 + 1) * 64 + lane];
+#pragma unroll
+                    for (int j = 0; j < JH; ++j) {
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(whi.v, P[ks][j0 + j].v, acc[j], 0, 0, 0);
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wlo.v, P[ks][j0 + j].v, acc[j], 0, 0, 0);
+                    }
                 }
-            }
-            if (q < Q) {
+                if (q < Q) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int seg = mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                    if (seg < p.S) {
-                        uint4 o;
-                        o.x = pack_bf16(acc[0][r], acc[1][r]);
-                        o.y = pack_bf16(acc[2][r], acc[3][r]);
-                        o.z = pack_bf16(acc[4][r], acc[5][r]);
-                        o.w = pack_bf16(acc[6][r], acc[7][r]);
-                        *reinterpret_cast<uint4 *>(p.slab + (size_t)seg * p.seg_stride + (size_t)q * 8) = o;
+                    for (int r = 0; r < 16; ++r) {
+                        const int seg = mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                        if (seg < p.S) {
+                            uint16_t *dst = p.slab + (size_t)seg * p.seg_stride + (size_t)q * 8 + j0;
+                            if constexpr (JH == 8) {
+                                uint4 o;
+                                o.x = pack_bf16(acc[0][r], acc[1][r]);
+                                o.y = pack_bf16(acc[2][r], acc[3][r]);
+                                o.z = pack_bf16(acc[4][r], acc[5][r]);
+                                o.w = pack_bf16(acc[6][r], acc[7][r]);
+                                *reinterpret_cast<uint4 *>(dst) = o;
+                            } else {
+                                uint2 o;
+                                o.x = pack_bf16(acc[0][r], acc[1][r]);
+                                o.y = pack_bf16(acc[2][r], acc[3][r]);
+                                *reinterpret_cast<uint2 *>(dst) = o;
+                            }
+                        }
                     }
                 }
             }
