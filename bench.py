@@ -90,9 +90,10 @@ def parse_args():
                          "after the headline run and reported beside it)")
     ap.add_argument("--single-mode", action="store_true", help="do not time the other merged-parameter mode")
     ap.add_argument("--slab-mb", type=int, default=0)
-    ap.add_argument("--fused", type=int, default=-1, choices=[-1, 0, 1, 2],
+    ap.add_argument("--fused", type=int, default=-1, choices=[-1, 0, 1, 2, 3],
                     help="lory_set_fused_merge: 0 slab pipeline only, 1 merge inside the GEMM for short segments "
-                         "(the library's default), 2 wherever the shape fits; -1 leaves the default")
+                         "(the library's default), 2 wherever the shape fits, 3 as 2 with the per-segment weight "
+                         "gradients kept on chip as well; -1 leaves the default")
     ap.add_argument("--verbose", action="store_true")
     ap.add_argument("--fwd-only", action="store_true",
                     help="time lory_route + lory_merged_ffn_fwd only (the forward configurations of the sweep)")

@@ -96,6 +96,13 @@ int lory_set_slab_budget(size_t bytes);
  *      traffic grows with the number of segments
  *   2  wherever the shape fits the kernel: T in {64, 128, 256}, E <= 32,
  *      B*L a multiple of 1024 (512 for T <= 128), no Wbar_save given
+ *   3  as 2, and the backward also keeps the per-segment weight gradients on
+ *      chip (expert gradients and routing-weight inner products accumulated by
+ *      the kernel that forms X_s^T dG_s; no gradient slab in HBM) where that
+ *      kernel takes the shape: E <= 16, T a multiple of 64, B*L/T a multiple of
+ *      8, bf16 gradients that overwrite (other calls use the slab pipeline for
+ *      this stage).  Measured slower than the slab pipeline at every shape tried;
+ *      it exists to be measured
  * The LORY_FUSED environment variable sets the initial value.  Changes what
  * lory_workspace_bytes reports (forward pass), so set it before sizing a
  * workspace.  Returns LORY_ERR_SHAPE for other values.

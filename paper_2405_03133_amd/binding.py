@@ -138,7 +138,8 @@ def lory_set_slab_budget(nbytes: int) -> None:
 
 
 def lory_set_fused_merge(mode: int) -> None:
-    """0 = slab pipeline only, 1 = merge inside the GEMM for short segments (default), 2 = wherever it fits."""
+    """0 = slab pipeline only, 1 = merge inside the GEMM for short segments (default), 2 = wherever it fits,
+    3 = as 2 and with the backward's per-segment weight gradients kept on chip."""
     _check(lib().lory_set_fused_merge(int(mode)), "lory_set_fused_merge")
 
 

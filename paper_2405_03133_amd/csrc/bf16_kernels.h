@@ -6,6 +6,7 @@
 #include "gemm2_bf16.h"
 #include "merge_scatter_bf16.h"
 #include "fused_bf16.h"
+#include "fused_bwd_bf16.h"
 
 namespace lory {
 namespace k {
@@ -136,6 +137,12 @@ void scatter_partial_dims(int S, int E, int *rows, int *cols);
 // merge inside the GEMM (fused_bf16.h): C = sum over nsrc sources of A_q * Wbar_q(segment of the row)
 bool fused_fits(const fmg::Params &p);
 hipError_t launch_fused(hipStream_t st, const fmg::Params &p, int nsrc, bool w_nc);
+
+// expert gradients and routing-weight inner products with the per-segment weight gradients kept on
+// chip (fused_bwd_bf16.h); the partial-sum buffer holds fused_dw_slots(p) x S x 16 floats
+bool fused_dw_fits(const fsg::Params &p);
+int fused_dw_slots(const fsg::Params &p);
+hipError_t launch_fused_dw(hipStream_t st, const fsg::Params &p);
 
 hipError_t launch_gu(hipStream_t st, const gemm::Params &p, const EpiGU &e);     // X * [Wg_bar | Wu_bar]
 hipError_t launch_down(hipStream_t st, const gemm::Params &p, const EpiStore &e);  // A * Wd_bar

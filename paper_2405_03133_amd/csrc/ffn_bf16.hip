@@ -50,7 +50,9 @@ size_t slab_budget_bytes()
 // Which shapes run their token contractions with the merge inside the GEMM (fused_bf16.h) instead
 // of the slab pipeline: 0 never, 1 where it measured faster (segments of at most 64 tokens with at
 // most 16 experts: the slab pipeline then moves four times the merged parameters of T = 256 through
-// HBM for a quarter of the rows each), 2 wherever the shape fits the kernel.
+// HBM for a quarter of the rows each), 2 wherever the shape fits the kernel, 3 like 2 and with the
+// backward's per-segment weight gradients kept on chip as well (fsg_kernel; measured slower than the
+// slab pipeline at every shape tried, so no other mode uses it).
 int g_fused_mode = -1;  // -1 = not initialised yet
 
 int fused_mode()
@@ -59,7 +61,7 @@ int fused_mode()
         int mode = 1;
         if (const char *env = getenv("LORY_FUSED")) {
             const long v = atol(env);
-            if (v >= 0 && v <= 2) mode = (int)v;
+            if (v >= 0 && v <= 3) mode = (int)v;
         }
         g_fused_mode = mode;
     }
@@ -88,8 +90,12 @@ bool use_fused(const Dims &m)
     const fmg::Params b = fused_params(m, nullptr, nullptr, m.dff, nullptr, nullptr, m.d, nullptr, m.d, m.dff,
                                        nullptr, m.d);
     if (!k::fused_fits(a) || !k::fused_fits(b)) return false;
-    return mode == 2 || (m.T <= 64 && m.E <= 16);
+    return mode >= 2 || (m.T <= 64 && m.E <= 16);
 }
+
+// Whether the backward keeps the per-segment weight gradients on chip as well (fsg_kernel), for
+// shapes that kernel takes.
+bool use_fused_dw() { return fused_mode() == 3; }
 
 // One fused contraction: C = sum over sources of A_q * Wbar_q(segment), merged on chip.
 hipError_t fused_gemm(hipStream_t st, const Dims &m, int cls, const fmg::Params &p, int nsrc, bool w_nc)
@@ -220,7 +226,7 @@ hipError_t gate_up_block(hipStream_t st, const Dims &m, int S, const bf *X, cons
 
 int set_fused_mode(int mode)
 {
-    if (mode < 0 || mode > 2) return LORY_ERR_SHAPE;
+    if (mode < 0 || mode > 3) return LORY_ERR_SHAPE;
     g_fused_mode = mode;
     return LORY_OK;
 }
@@ -391,6 +397,20 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
     // token contractions with the merge inside the GEMM (no re-merged slabs); the per-segment weight
     // gradients still pass through the slab
     const bool fused = !Wbar && m.S <= pl.Sc && use_fused(m);
+    // ... unless the expert-gradient kernel that keeps them on chip takes the shape (bf16 gradients
+    // that overwrite; at most 16 experts)
+    auto dw_params = [&](const bf *A, int lda, const bf *B, int ldb, const bf *W, void *dW, int M, int N) {
+        fsg::Params q = {};
+        q.A = (const uint16_t *)A; q.lda = lda;
+        q.B = (const uint16_t *)B; q.ldb = ldb;
+        q.W = (const uint16_t *)W; q.dW = (uint16_t *)dW;
+        q.expert_stride = (long)m.D; q.ldw = N;
+        q.w = w; q.E = m.E; q.T = m.T; q.S = m.S; q.M = M; q.N = N;
+        return q;
+    };
+    const bool fused_dw = fused && use_fused_dw() && !grad_f32 && !accumulate &&
+                          k::fused_dw_fits(dw_params(nullptr, m.dff, nullptr, m.d, nullptr, nullptr, m.dff, m.d)) &&
+                          k::fused_dw_fits(dw_params(nullptr, m.d, nullptr, m.dff, nullptr, nullptr, m.d, m.dff));
 
     for (int s0 = 0; s0 < m.S; s0 += pl.Sc) {
         const int S = (m.S - s0 < pl.Sc) ? (m.S - s0) : pl.Sc;
@@ -432,8 +452,29 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
             LORY_TRY(k::launch_swiglu_bwd(st, Gc, Uc, dG, dU, Act, m.tokens, m.dff, 0, m.dff));
         }
 
+        if (fused_dw) {
+            // expert gradients and routing-weight inner products of the three matrices, the per-segment
+            // weight gradients never leaving the CU; every workgroup-wave adds its inner products
+            // to a slot of its own, matrix after matrix
+            fsg::Params q[3] = {dw_params(Act, m.dff, dY, m.d, Wd, dWd, m.dff, m.d),
+                                dw_params(X, m.d, dG, m.dff, Wg, dWg, m.d, m.dff),
+                                dw_params(X, m.d, dU, m.dff, Wu, dWu, m.d, m.dff)};
+            int slots = 0;
+            for (int i = 0; i < 3; ++i) {
+                q[i].partials = partials;
+                q[i].partials_add = i > 0;
+                slots = k::fused_dw_slots(q[i]);   // the same for the three matrices (M N is)
+                const double n = (double)m.D;
+                prof::Range r(st, prof::kFusedDW, 2.0 * m.tokens * n + 8.0 * m.S * 16 * n,
+                              2.0 * (2.0 * m.E * n + (double)m.tokens * (m.d + m.dff)));
+                LORY_TRY(k::launch_fused_dw(st, q[i]));
+            }
+            prof::Range r(st, prof::kDwReduce, (double)slots * m.S * m.E, 4.0 * slots * m.S * 16);
+            LORY_TRY(k::launch_dw_reduce(st, partials, slots, m.S, 16, dw, m.S, m.E));
+        }
+
         // ---- d_ff blocks: dA (+ SwiGLU backward), weight-gradient slabs, scatter
-        for (int n0 = 0; n0 < m.dff; n0 += pl.nf_bwd) {
+        for (int n0 = 0; !fused_dw && n0 < m.dff; n0 += pl.nf_bwd) {
             const int nf = (m.dff - n0 < pl.nf_bwd) ? (m.dff - n0) : pl.nf_bwd;
             const size_t blk = (size_t)S * m.d * nf;  // elements of one slab of this block
             bf *s_md = slab, *s_gd = slab + blk, *s_gg = slab + 2 * blk, *s_gu = slab + 3 * blk;
@@ -535,10 +576,12 @@ int bf16_ffn_bwd(const Dims &m, const void *Xv, const float *w, const void *Wgv,
             LORY_TRY(k::launch_dx(st, p, epi));
         }
 
-        int prow, pcol;
-        k::scatter_partial_dims(S, m.E, &prow, &pcol);
-        prof::Range r(st, prof::kDwReduce, (double)grid * S * m.E, 4.0 * grid * prow * pcol);
-        LORY_TRY(k::launch_dw_reduce(st, partials, grid, prow, pcol, dw + (size_t)s0 * m.E, S, m.E));
+        if (!fused_dw) {
+            int prow, pcol;
+            k::scatter_partial_dims(S, m.E, &prow, &pcol);
+            prof::Range r(st, prof::kDwReduce, (double)grid * S * m.E, 4.0 * grid * prow * pcol);
+            LORY_TRY(k::launch_dw_reduce(st, partials, grid, prow, pcol, dw + (size_t)s0 * m.E, S, m.E));
+        }
     }
     return LORY_OK;
 }

@@ -43,7 +43,8 @@ inline int launch_status()
 // ---- optional event timing per kernel class (profile.hip)
 namespace prof {
 enum Class { kRoute = 0, kMerge, kGemmGU, kSwigluFwd, kGemmDown, kGemmDA, kSwigluBwd, kGemmDX, kGemmDWGU, kGemmDWD, kScatter,
-             kDwReduce, kRouteBwd, kDenseSkinny, kFusedGU, kFusedDown, kFusedDA, kFusedDX, kNumClasses };
+             kDwReduce, kRouteBwd, kDenseSkinny, kFusedGU, kFusedDown, kFusedDA, kFusedDX, kFusedDW,
+             kNumClasses };
 bool enabled();
 int set_enabled(int on);
 int read(lory_kernel_stat *out, int max_out, int *n_out);

@@ -27,7 +27,7 @@ std::vector<hipEvent_t> g_pool;
 const char *const kNames[kNumClasses] = {"route",     "merge",     "gemm_gate_up", "swiglu_fwd", "gemm_down",
                                          "gemm_dA",   "swiglu_bwd", "gemm_dX",   "gemm_dW_gate_up",
                                          "gemm_dW_down", "scatter_dots", "dw_reduce", "route_bwd", "dense_skinny",
-                                         "fused_gate_up", "fused_down", "fused_dA", "fused_dX"};
+                                         "fused_gate_up", "fused_down", "fused_dA", "fused_dX", "fused_dW_dots"};
 
 // Events are created when timing is switched on (and by lory_profile_read, which returns
 // them to the pool), never inside a launch: a launch only takes events from the pool and

@@ -56,7 +56,7 @@ int main()
         }
     }
     EXPECT(lory_set_slab_budget(1024) == LORY_ERR_SHAPE);
-    EXPECT(lory_set_fused_merge(3) == LORY_ERR_SHAPE && lory_set_fused_merge(-1) == LORY_ERR_SHAPE);
+    EXPECT(lory_set_fused_merge(4) == LORY_ERR_SHAPE && lory_set_fused_merge(-1) == LORY_ERR_SHAPE);
     EXPECT(lory_set_slab_budget((size_t)6144 << 20) == LORY_OK && lory_set_fused_merge(1) == LORY_OK);
 
     size_t out = 0;

@@ -40,11 +40,13 @@ ID_TOL = 3e-2
 # configuration (G/U saved, the backward re-merges; short segments take the merge-inside-the-GEMM
 # kernels by the library's own rule), "saved" = merged parameters handed to the backward (bench.py
 # --merged-save), "fwd" = route + forward with nothing saved, "fused" = as "remerge" with the
-# merge-inside-the-GEMM kernels forced on (bench.py --fused 2).
+# merge-inside-the-GEMM kernels forced on (bench.py --fused 2), "fused_all" = with the expert-gradient
+# kernel that keeps the per-segment weight gradients on chip as well (bench.py --fused 3).
 CASES = [
     ("C4", "remerge", False),
     ("C4", "fused", False),
     ("C5_T128", "fused", True),
+    ("C5_T64", "fused_all", False),
     ("C4", "saved", True),
     ("C2", "fwd", False),
     ("C3", "remerge", True),
@@ -76,7 +78,7 @@ def test_full_size_sampled(name, mode, structured):
     dev = {k: torch.from_numpy(v).cuda().to(torch.bfloat16).contiguous() for k, v in t.items()}
     shape = lb.make_shape(cfg.B, cfg.L, cfg.T, cfg.d, cfg.d_ff, cfg.E, torch.bfloat16)
     print("[full] running GPU route/fwd/bwd", flush=True)
-    lb.lory_set_fused_merge(2 if mode == "fused" else 1)
+    lb.lory_set_fused_merge({"fused": 2, "fused_all": 3}.get(mode, 1))
     try:
         results = _run_gpu(cfg, dev, shape, mode)
     finally:

@@ -286,6 +286,49 @@ def test_bf16_fused_merge_gemm(cfg, save, fused_everywhere, default_budget):
         assert np.array_equal(got[key], again[key]), key
 
 
+@pytest.fixture
+def fused_with_gradients():
+    lb.lory_set_fused_merge(3)
+    yield
+    lb.lory_set_fused_merge(1)
+
+
+# shapes the expert-gradient kernel takes (at most 16 experts, T a multiple of 64, B L / T a multiple
+# of 8); the last one has three tiles along each matrix dimension and experts beyond E in the operand
+FSG_CASES = [c for c in FUSED_CASES if c.name in ("fused_T256", "fused_T64", "fused_T64_E11", "fused_T64_E5",
+                                                  "fused_many_tasks")]
+
+
+@pytest.mark.parametrize("cfg", FSG_CASES, ids=lambda c: c.name)
+@pytest.mark.parametrize("save", [True, False], ids=["saved_GU", "recompute_GU"])
+def test_bf16_fused_expert_gradients(cfg, save, fused_with_gradients, default_budget):
+    """As above, and with the per-segment weight gradients kept on chip: expert gradients and
+    routing-weight gradients from the kernel that forms X_s^T dG_s; bit-reproducible (every wave adds
+    its inner products to a slot of its own, and the slots are summed in a fixed order)."""
+    assert cfg.E <= 16 and cfg.T % 64 == 0 and cfg.S % 8 == 0
+    t = make_inputs(cfg, structured=True)
+    got = run_layer(cfg, t, save=save, grad_dtype=torch.bfloat16)
+    ref = oracle_layer(cfg, t, got["w_used"])
+    names = ALL if save else ("Y", "dX", "dWg", "dWu", "dWd", "dw")
+    compare(cfg, got, ref, names, TOL["bf16"])
+    again = run_layer(cfg, t, save=save, grad_dtype=torch.bfloat16)
+    for key in names:
+        assert np.array_equal(got[key], again[key]), key
+
+
+def test_bf16_fused_expert_gradients_differ_from_slab_path_only_by_rounding(fused_with_gradients, default_budget):
+    """The same call with the slab pipeline for the weight stage (mode 2): the two agree to bf16
+    rounding, which shows that mode 3 ran another kernel and that both compute the same thing."""
+    cfg = FUSED_CASES[3]
+    t = make_inputs(cfg, structured=True)
+    on_chip = run_layer(cfg, t, grad_dtype=torch.bfloat16)
+    lb.lory_set_fused_merge(2)
+    slab = run_layer(cfg, t, grad_dtype=torch.bfloat16)
+    for key in ("dWg", "dWu", "dWd", "dw"):
+        check(f"{cfg.name} {key} on chip vs slab", on_chip[key], slab[key], TOL["bf16"])
+    assert any(not np.array_equal(on_chip[k], slab[k]) for k in ("dWg", "dWu", "dWd"))
+
+
 def test_bf16_fused_onehot_routing(fused_everywhere):
     """One-hot routing weights select exactly one expert: the fused kernel's merged tiles are then
     copies of that expert's (bf16 values pass through the hi + lo weight pair unchanged)."""
