@@ -8,8 +8,8 @@
 //
 // A workgroup (4 wavefronts, one per CU) owns a 64 x 64 tile of the matrix for all experts: its
 // 16 x 4096 fp32 expert-gradient accumulators are all of the CU's accumulation registers.  It walks
-// the token stream once, 64 tokens per step through a six-stage ring of direct global->LDS loads
-// shared by the four waves (five steps, 80 KB, in flight: a step has only four MFMAs per wave, so
+// the token stream once, 64 tokens per step through a five-stage ring of direct global->LDS loads
+// shared by the four waves (four steps, 64 KB, in flight: a step has only four MFMAs per wave, so
 // the ring has to cover the whole load latency); wave (wm, wn) multiplies its 32 x 32 block.  At the end of a segment the
 // block P_s (the segment's weight gradient) is rounded to bf16 and written to LDS as
 // P[cell][segment of the group]; after every eighth segment the wave
@@ -18,11 +18,12 @@
 //     cell's 16-byte row);
 //   * forms < W[e], P_s > for its elements: 32 MFMAs 16x16x32, rows = experts, columns = segments,
 //     K = 32 cells (operand: two transposing LDS reads of four cells' rows each); the wave's part of
-//     the W tile sits in 128 registers for the whole task; the sums are added to the wave's own
-//     slot of a partial-sum buffer (fixed order: reproducible).
+//     the W tile stays on chip for the whole task, 112 registers and 4 KB of LDS; the sums are added
+//     to the wave's own slot of a partial-sum buffer (fixed order: reproducible).
 // Everything after the ring is wave-private: no barrier besides the ring's.
 //
-// LDS (160 KB): ring 6 x 16 KB | P: per wave [1024 cells][8 segments] bf16.
+// LDS (160 KB): ring 5 x 16 KB | P: per wave [1024 cells][8 segments] bf16 | per wave 8 K blocks of
+// the W tile ([block][lane] x 8 bytes).
 //   cell c = ((r >> 2) * 2 + h) * 128 + (r & 3) * 32 + m       accumulator element r of lane (m, h):
 //            row m, column 8 (r >> 2) + 4 h + (r & 3) of the wave's block
 //   K block j of the inner products, operand lane (x, kg), element t: cell (j >> 3) * 128 + t * 32 +
@@ -45,12 +46,14 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kThreads = 256;
 constexpr int BT = 64;                    // tile edge
 constexpr int BK = 64;                    // tokens per step
-constexpr int kStages = 6;
+constexpr int kStages = 5;
 constexpr int kOperand = BK * BT * 2;     // 8 KB: 64 token rows of 64 columns
 constexpr int kStage = 2 * kOperand;      // A + B
-constexpr int kRing = kStages * kStage;   // 96 KB
+constexpr int kRing = kStages * kStage;   // 80 KB
 constexpr int kP = 16 * 1024;             // one wave's P region
-constexpr int kLds = kRing + 4 * kP;      // 160 KB
+constexpr int kWRegs = 56;                // K blocks of the W tile held in registers; the other 8 in LDS
+constexpr int kWL = (64 - kWRegs) * 512;  // one wave's part of the W tile in LDS: 4 KB
+constexpr int kLds = kRing + 4 * kP + 4 * kWL;   // 160 KB
 constexpr int kSegments = 8;              // segments per group step
 
 struct Params {
@@ -97,6 +100,7 @@ __global__ __launch_bounds__(kThreads, 1) void fsg_kernel(const Params p)
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
     char *P1 = smem + kRing + wave * kP;
+    char *WL = smem + kRing + 4 * kP + wave * kWL;
     float *slot = p.partials + ((size_t)blockIdx.x * 4 + wave) * (size_t)p.S * 16;
 
     const int ml = lane & 31, h = lane >> 5;      // accumulator lane of the 32 x 32 block
@@ -136,7 +140,7 @@ __global__ __launch_bounds__(kThreads, 1) void fsg_kernel(const Params p)
             // ---- the wave's part of the expert tile, as operands of the inner-product MFMAs:
             //      K block j, lane (e = x, kg): elements 16 j + 4 kg .. + 3, i.e. row 4 (j & 7) + kg,
             //      columns 8 (j >> 4) + 4 ((j >> 3) & 1) .. + 3 of the wave's 32 x 32 block
-            u32x2 Wreg[64];
+            u32x2 Wreg[kWRegs];
             {
                 const int e = x < p.E ? x : 0;
                 const uint16_t *wb = p.W + (size_t)e * p.expert_stride + (size_t)(m0 + wm * 32) * p.ldw + n0 + wn * 32;
@@ -145,7 +149,10 @@ __global__ __launch_bounds__(kThreads, 1) void fsg_kernel(const Params p)
                     const int row = 4 * (j & 7) + kg, col = 8 * (j >> 4) + 4 * ((j >> 3) & 1);
                     u32x2 v = *reinterpret_cast<const u32x2 *>(wb + (size_t)row * p.ldw + col);
                     if (x >= p.E) v = u32x2{0u, 0u};
-                    Wreg[j] = v;
+                    if (j < kWRegs)
+                        Wreg[j] = v;
+                    else
+                        *reinterpret_cast<u32x2 *>(WL + (j - kWRegs) * 512 + lane * 8) = v;
                 }
             }
 
@@ -155,6 +162,7 @@ __global__ __launch_bounds__(kThreads, 1) void fsg_kernel(const Params p)
             f32x16 acc_p;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc_p[r] = 0.f;
+            uint32_t even[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};   // an even segment's block as bf16 pairs
 
             const uint16_t *src = loads_a ? p.A + m0 : p.B + n0;
             const int ld = loads_a ? p.lda : p.ldb;
@@ -165,19 +173,17 @@ __global__ __launch_bounds__(kThreads, 1) void fsg_kernel(const Params p)
                     gemm2::dma16(src + (size_t)(g * BK + ld_row[i]) * ld + ld_col[i], dst + i * 1024);
             };
 
-            // ring: five steps ahead
+            // ring: four steps ahead
 #pragma unroll
             for (int i = 0; i < kStages - 1; ++i)
                 if (i < G) issue(i, i);
-            int g = 0, stage = 0;   // step, its ring stage (g mod 6)
+            int g = 0, stage = 0;   // step, its ring stage (g mod 5)
             for (int s0 = 0; s0 < p.S; s0 += kSegGroup) {
                 for (int sl = 0; sl < kSegGroup; ++sl) {
                     for (int ks = 0; ks < steps_per_seg; ++ks, ++g) {
-                        // own loads of step g have landed (four per step; up to four later steps pending)
+                        // own loads of step g have landed (four per step; up to three later steps pending)
                         const int later = G - 1 - g;
-                        if (later >= 4)
-                            gemm2::wait_vmcnt<16>();
-                        else if (later == 3)
+                        if (later >= 3)
                             gemm2::wait_vmcnt<12>();
                         else if (later == 2)
                             gemm2::wait_vmcnt<8>();
@@ -198,18 +204,26 @@ __global__ __launch_bounds__(kThreads, 1) void fsg_kernel(const Params p)
                             acc_p = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr, af, acc_p, 0, 0, 0);
                         }
                     }
-                    // ---- end of segment s0 + sl: acc_p element r = row ml, column 8 (r >> 2) + 4 h + (r & 3)
+                    // ---- end of segment s0 + sl: acc_p element r = row ml, column 8 (r >> 2) + 4 h + (r & 3).
+                    //      An even segment waits in registers for the odd one: 4-byte stores of a segment
+                    //      pair (the cells are 16 bytes apart, four lanes share a bank).
 #pragma unroll
                     for (int rq = 0; rq < 4; ++rq) {
                         const uint32_t lo = gemm::cvt_pk_bf16(acc_p[rq * 4 + 0], acc_p[rq * 4 + 1]);
                         const uint32_t hi = gemm::cvt_pk_bf16(acc_p[rq * 4 + 2], acc_p[rq * 4 + 3]);
-                        const int cb = (rq * 2 + h) * 128;
-                        // P[cell][segment]
-                        uint16_t *p1 = reinterpret_cast<uint16_t *>(P1) + sl;
-                        p1[(cb + 0 * 32 + ml) * 8] = (uint16_t)(lo & 0xffffu);
-                        p1[(cb + 1 * 32 + ml) * 8] = (uint16_t)(lo >> 16);
-                        p1[(cb + 2 * 32 + ml) * 8] = (uint16_t)(hi & 0xffffu);
-                        p1[(cb + 3 * 32 + ml) * 8] = (uint16_t)(hi >> 16);
+                        if ((sl & 1) == 0) {
+                            even[rq * 2 + 0] = lo;
+                            even[rq * 2 + 1] = hi;
+                        } else {
+                            const int cb = (rq * 2 + h) * 128;
+                            // P[cell][segment]: segments sl - 1 (low half) and sl
+                            uint32_t *p1 = reinterpret_cast<uint32_t *>(P1) + (sl >> 1);
+                            const uint32_t el = even[rq * 2 + 0], eh = even[rq * 2 + 1];
+                            p1[(cb + 0 * 32 + ml) * 4] = __builtin_amdgcn_perm(lo, el, 0x05040100u);
+                            p1[(cb + 1 * 32 + ml) * 4] = __builtin_amdgcn_perm(lo, el, 0x07060302u);
+                            p1[(cb + 2 * 32 + ml) * 4] = __builtin_amdgcn_perm(hi, eh, 0x05040100u);
+                            p1[(cb + 3 * 32 + ml) * 4] = __builtin_amdgcn_perm(hi, eh, 0x07060302u);
+                        }
                     }
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc_p[r] = 0.f;
@@ -259,7 +273,10 @@ __global__ __launch_bounds__(kThreads, 1) void fsg_kernel(const Params p)
 #pragma unroll
                         for (int u = 0; u < 2; ++u) {
                             const int j = 2 * jj + u;
-                            wj.u[u] = Wreg[j];
+                            if (j < kWRegs)
+                                wj.u[u] = Wreg[j];
+                            else
+                                wj.u[u] = *reinterpret_cast<const u32x2 *>(WL + (j - kWRegs) * 512 + lane * 8);
                             pj.h[u] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                                 (lds_ptr)(pt + ((j >> 3) * 128 + 4 * (j & 7)) * 16));
                         }
