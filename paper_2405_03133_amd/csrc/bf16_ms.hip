@@ -89,7 +89,8 @@ hipError_t launch_scatter(hipStream_t st, const ms::ScatterParams &p, int grid)
 #define LORY_SCATTER(K, B)                                                                            \
     do {                                                                                              \
         const size_t lds_red = (size_t)4 * K * B * 1024;                                              \
-        const size_t lds = lds_main > lds_red ? lds_main : lds_red;                                   \
+        const size_t lds_work = lds_main + (ms::scatter_parks_experts<K, B>() ? 4 * B * 4096 : 0);    \
+        const size_t lds = lds_work > lds_red ? lds_work : lds_red;                                   \
         auto kern = ms::scatter_kernel<K, B>;                                                         \
         if (lds > 48 * 1024) {                                                                        \
             static bool configured = false;                                                           \

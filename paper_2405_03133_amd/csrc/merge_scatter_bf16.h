@@ -250,16 +250,26 @@ constexpr int kDotPitch = 272;  // bytes per segment row of a wave's LDS staging
 //   (2) walks the segments 16 at a time (next block's loads in flight behind the MFMAs),
 //   (3) writes 32 experts x 128 elements of expert gradients.
 // Dynamic LDS: the larger of KB * 2 * 64 * 16 bytes of routing-weight operands + 4 * 16 * kDotPitch
-// and 4 * KBM * EB16 * 1024 bytes for the final reduction of the router-weight accumulators.
+// (+ 4 * EB16 * 4096 when the expert chunks are parked, below) and 4 * KBM * EB16 * 1024 bytes for the
+// final reduction of the router-weight accumulators.
+// Two workgroups per CU wherever a wave stays under 256 registers: up to 8 blocks of router-weight
+// accumulators, and 16 blocks (129-256 segments with at most 16 experts: the short-segment shapes,
+// 3.7 -> 4.9 TB/s; 65-128 segments with 17-32 experts) with the unit's expert chunks parked in LDS
+// instead of 16 or 32 registers.
 template <int KBM, int EB16>
-__global__ __launch_bounds__(256, (KBM * EB16 <= 8) ? 2 : 1) void scatter_kernel(const ScatterParams p)
+constexpr bool scatter_parks_experts() { return KBM * EB16 == 16; }
+
+template <int KBM, int EB16>
+__global__ __launch_bounds__(256, (KBM * EB16 <= 8 || scatter_parks_experts<KBM, EB16>()) ? 2 : 1) void scatter_kernel(const ScatterParams p)
 {
+    constexpr bool kParkB = scatter_parks_experts<KBM, EB16>();
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, hh = (lane >> 4) & 1, sh = lane >> 5;
     const int KB = (p.S + 15) >> 4;
     uint4 *wtab = reinterpret_cast<uint4 *>(smem);  // [kb][hi/lo][lane]
     char *park = smem + (size_t)KB * 2 * 64 * 16 + wave * (16 * kDotPitch);
+    char *parkB = smem + (size_t)KB * 2 * 64 * 16 + 4 * (16 * kDotPitch) + wave * (EB16 * 4096);   // kParkB only
     const int Ewin = (p.E - p.e0 < 32) ? (p.E - p.e0) : 32;
 
     for (int idx = tid; idx < KB * 64; idx += 256) {
@@ -310,6 +320,14 @@ __global__ __launch_bounds__(256, (KBM * EB16 <= 8) ? 2 : 1) void scatter_kernel
                 else
                     Bst[b][kq].u = make_uint4(0, 0, 0, 0);
             }
+        }
+        if constexpr (kParkB) {
+            // (the previous unit's reads of this area have returned: LDS operations of a wave stay in order)
+#pragma unroll
+            for (int b = 0; b < EB16; ++b)
+#pragma unroll
+                for (int kq = 0; kq < 4; ++kq)
+                    *reinterpret_cast<uint4 *>(parkB + (b * 4 + kq) * 1024 + lane * 16) = Bst[b][kq].u;
         }
 
         f32x16 acc[4];
@@ -368,9 +386,12 @@ __global__ __launch_bounds__(256, (KBM * EB16 <= 8) ? 2 : 1) void scatter_kernel
                     af.u = *reinterpret_cast<const uint4 *>(park + (lane & 15) * kDotPitch +
                                                             (4 * kq + (lane >> 4)) * 16);
 #pragma unroll
-                    for (int b = 0; b < EB16; ++b)
-                        dots[kb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af.v, Bst[b][kq].v, dots[kb][b],
-                                                                             0, 0, 0);
+                    for (int b = 0; b < EB16; ++b) {
+                        Frag bf = Bst[b][kq];
+                        if constexpr (kParkB)
+                            bf.u = *reinterpret_cast<const uint4 *>(parkB + (b * 4 + kq) * 1024 + lane * 16);
+                        dots[kb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af.v, bf.v, dots[kb][b], 0, 0, 0);
+                    }
                 }
                 __builtin_amdgcn_wave_barrier();
             }

@@ -163,6 +163,9 @@ BF16_CASES = [
     (LoryConfig("bf16_S256_T64_E16", B=4, L=4096, T=64, d=128, d_ff=256, E=16, dtype="bf16", seed=38), 128 << 20),
     (LoryConfig("bf16_T1024_E16", B=1, L=2048, T=1024, d=128, d_ff=256, E=16, dtype="bf16", seed=39), 128 << 20),
     (LoryConfig("bf16_S300_E64", B=5, L=3840, T=64, d=64, d_ff=128, E=64, dtype="bf16", seed=40), 128 << 20),
+    # 129-256 segments with at most 16 experts: the scatter instance that parks its expert chunks in LDS,
+    # here with fewer 16-segment blocks than its static bound
+    (LoryConfig("bf16_S160_E12", B=5, L=2048, T=64, d=64, d_ff=128, E=12, dtype="bf16", seed=44), 128 << 20),
     # every GEMM on the persistent ring kernel with two tiles per workgroup (tile boundaries inside
     # the K-step stream), all outputs compared element by element
     (LoryConfig("bf16_ring_two_tiles", B=4, L=4096, T=256, d=512, d_ff=1024, E=4, dtype="bf16", seed=43),
