@@ -88,6 +88,12 @@ for _T in (64, 128, 256, 512, 1024):
                                       dtype="bf16", seed=_BASE_SEED + 5)
 
 
+# The headline shape with short segments (Appendix B's E/T overhead at its largest: E = 32, T = 64 and 128).
+for _T in (64, 128):
+    CONFIGS[f"C4_T{_T}"] = LoryConfig(f"C4_T{_T}", B=4, L=4096, T=_T, d=2048, d_ff=5632, E=32,
+                                      dtype="bf16", seed=_BASE_SEED + 9)
+
+
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
     """Round float32 values to the nearest bfloat16 (ties to even) and return
     them widened back to float32 (the widening is exact)."""

@@ -60,6 +60,7 @@ CASES = [
     ("P15_E16", "remerge", False),
     ("P15_E32", "remerge", True),
     ("P7_E4", "remerge", False),
+    ("C4_T64", "remerge", False),
 ]
 
 
